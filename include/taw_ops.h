@@ -1,0 +1,76 @@
+/* taw_ops.h -- kernel-level entry points of the decoder-layer library.
+ *
+ * taw_layer_fwd / taw_layer_bwd (taw.h) are sequences of the operations below; these entry
+ * points launch one of them on its own so that each kernel can be checked against the matching
+ * step of the layer definition and timed against its roofline.  Same rules as taw.h: device
+ * pointers, 16-byte aligned, caller-owned, enqueued on `stream`, int status returned, all
+ * validation on the host before the launch.  `dtype` is a taw_dtype (storage of activations and
+ * weights); arithmetic is fp32 with fp32 accumulation (bf16 MFMA products accumulate in fp32).
+ *
+ * `impl` selects the kernel family: TAW_IMPL_AUTO picks the MFMA kernel when the shape allows it
+ * (bf16, dimensions multiples of 8; attention: head_dim 128) and the shape-generic kernel
+ * otherwise; TAW_IMPL_GENERIC / TAW_IMPL_MFMA force one and return TAW_ERR_UNSUPPORTED when it
+ * cannot take the shape.
+ */
+#ifndef TAW_OPS_H
+#define TAW_OPS_H
+
+#include "taw.h"
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum { TAW_IMPL_AUTO = 0, TAW_IMPL_GENERIC = 1, TAW_IMPL_MFMA = 2 };
+enum { TAW_GEMM_NT = 0, TAW_GEMM_NN = 1, TAW_GEMM_TN = 2 };
+
+/* The three products of a linear layer y = x W^T (W is [out, in]):
+ *   TAW_GEMM_NT  C[M,N] = A[M,K] B[N,K]^T     forward,          y  = x W^T
+ *   TAW_GEMM_NN  C[M,N] = A[M,K] B[K,N]       input gradient,   dx = dy W
+ *   TAW_GEMM_TN  C[M,N] = A[K,M]^T B[K,N]     weight gradient,  dW = dy^T x  (contraction over tokens)
+ * lda/ldb/ldc/ldr are row strides in elements.  C has storage type c_dtype (dtype or TAW_F32);
+ * accumulate != 0 adds the product into C (the fp32 gradient-shard update G += dW).
+ * R (may be NULL) is a residual of C's type and shape added to the product (h = x + o Wo^T). */
+int taw_op_gemm(int32_t dtype, int32_t mode, int64_t M, int64_t N, int64_t K, const void* A, int64_t lda,
+                const void* B, int64_t ldb, void* C, int64_t ldc, int32_t c_dtype, int32_t accumulate,
+                const void* R, int64_t ldr, int32_t impl, void* stream);
+
+/* r[t] = 1/sqrt(mean_i x[t,i]^2 + eps);  out[t,i] = x[t,i] r[t] gamma[i].   x,out [T,H]; r fp32 [T]. */
+int taw_op_rmsnorm_fwd(int32_t dtype, int64_t T, int32_t H, const void* x, const void* gamma, float eps,
+                       void* out, float* r, void* stream);
+
+/* Gradient of the above through z (the forward input), plus an optional residual gradient:
+ *   c = dout*gamma;  dz = r c - z r^3 mean_j(c_j z_j) + (dres ? dres : 0)
+ *   dgamma[i] (=|+=) sum_t dout[t,i] z[t,i] r[t]      (fp32 [H]; += when accumulate != 0)
+ * scratch: fp32, taw_op_rmsnorm_bwd_scratch_floats(H) elements. */
+size_t taw_op_rmsnorm_bwd_scratch_floats(int32_t H);
+int taw_op_rmsnorm_bwd(int32_t dtype, int64_t T, int32_t H, const void* dout, const void* z, const float* r,
+                       const void* gamma, const void* dres, void* dz, float* dgamma, int32_t accumulate,
+                       float* scratch, void* stream);
+
+/* Rotary embedding in place on columns [0, ncols) of z [B*S, ld]; ncols a multiple of head_dim.
+ * Pair (2i, 2i+1) of each head at position p turns by p*theta^(-2i/d); inverse != 0 turns back
+ * (the backward map). */
+int taw_op_rope(int32_t dtype, int32_t B, int32_t S, int32_t ncols, int32_t head_dim, void* z, int64_t ld,
+                const float* rope_table, int32_t inverse, void* stream);
+
+/* gu = [gate | up] [T, 2I];  a [T, I] = gate*sigmoid(gate)*up.  Backward: dgu [T, 2I] from da [T, I]. */
+int taw_op_swiglu_fwd(int32_t dtype, int64_t T, int32_t I, const void* gu, void* a, void* stream);
+int taw_op_swiglu_bwd(int32_t dtype, int64_t T, int32_t I, const void* da, const void* gu, void* dgu, void* stream);
+
+/* Causal softmax attention on qkv [B*S, 3H] (q | k | v; head h = columns h*d..h*d+d-1 of each
+ * part; q and k already rotated), scale 1/sqrt(d), keys u <= t.  Writes o [B*S, H] and
+ * lse [B, n_heads, S] (fp32, natural log of the row's sum of exponentials of scaled scores). */
+int taw_op_attn_fwd(int32_t dtype, int32_t B, int32_t S, int32_t n_heads, int32_t head_dim, const void* qkv,
+                    void* o, float* lse, int32_t impl, void* stream);
+
+/* Its gradient: dqkv [B*S, 3H] from dO [B*S, H], recomputing the probabilities from qkv and lse.
+ * scratch: fp32, B*n_heads*S elements (holds D[t] = dO[t].o[t]). */
+int taw_op_attn_bwd(int32_t dtype, int32_t B, int32_t S, int32_t n_heads, int32_t head_dim, const void* qkv,
+                    const void* o, const void* dO, const float* lse, void* dqkv, float* scratch,
+                    int32_t impl, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TAW_OPS_H */

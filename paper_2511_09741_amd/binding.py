@@ -1,0 +1,204 @@
+"""ctypes binding over libtaw.so: the same names as include/taw.h and include/taw_ops.h.
+
+Argument marshalling only.  Device buffers are torch tensors (torch owns device memory and
+streams); every function takes their data pointers, calls the C entry point and raises TawError
+on a non-zero status.  There is no fallback: if the library is missing, load() raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libtaw.so")
+
+TAW_F32, TAW_BF16 = 0, 1
+TAW_ACCUMULATE = 1
+TAW_IMPL_AUTO, TAW_IMPL_GENERIC, TAW_IMPL_MFMA = 0, 1, 2
+TAW_GEMM_NT, TAW_GEMM_NN, TAW_GEMM_TN = 0, 1, 2
+TAW_OK = 0
+TAW_ERR_NULL, TAW_ERR_SHAPE, TAW_ERR_DTYPE, TAW_ERR_ALIGN, TAW_ERR_WORKSPACE, TAW_ERR_UNSUPPORTED, TAW_ERR_HIP = -1, -2, -3, -4, -5, -6, -7
+
+LAYOUT_FIELDS = ("gamma_attn", "w_qkv", "w_o", "gamma_mlp", "w_gate_up", "w_down", "total_elems")
+
+
+class taw_layer_desc(C.Structure):
+    _fields_ = [("dtype", C.c_int32), ("B", C.c_int32), ("S", C.c_int32), ("H", C.c_int32),
+                ("n_heads", C.c_int32), ("head_dim", C.c_int32), ("I", C.c_int32),
+                ("rope_theta", C.c_float), ("rms_eps", C.c_float), ("flags", C.c_uint32)]
+
+
+class taw_weight_layout(C.Structure):
+    _fields_ = [(f, C.c_size_t) for f in LAYOUT_FIELDS]
+
+
+class TawError(RuntimeError):
+    def __init__(self, status: int, name: str, detail: str):
+        super().__init__(f"{name} ({status}): {detail}")
+        self.status = status
+
+
+_lib = None
+
+_vp, _i32, _i64, _sz, _f = C.c_void_p, C.c_int32, C.c_int64, C.c_size_t, C.c_float
+_dp = C.POINTER(taw_layer_desc)
+_SIGS = {
+    "taw_layer_weight_layout": (C.c_int, [_dp, C.POINTER(taw_weight_layout)]),
+    "taw_layer_ctx_bytes": (_sz, [_dp]),
+    "taw_layer_workspace_bytes": (_sz, [_dp]),
+    "taw_rope_table_init": (C.c_int, [_dp, _vp, _vp]),
+    "taw_layer_fwd": (C.c_int, [_dp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "taw_layer_bwd": (C.c_int, [_dp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "taw_grad_accum": (C.c_int, [_vp, _vp, _i32, _sz, _f, _vp]),
+    "taw_weight_stage": (C.c_int, [_vp, _vp, _sz, _vp, _vp, _vp]),
+    "taw_status_string": (C.c_char_p, [C.c_int]),
+    "taw_last_error": (C.c_char_p, []),
+    "taw_op_gemm": (C.c_int, [_i32, _i32, _i64, _i64, _i64, _vp, _i64, _vp, _i64, _vp, _i64, _i32, _i32, _vp, _i64, _i32, _vp]),
+    "taw_op_rmsnorm_fwd": (C.c_int, [_i32, _i64, _i32, _vp, _vp, _f, _vp, _vp, _vp]),
+    "taw_op_rmsnorm_bwd_scratch_floats": (_sz, [_i32]),
+    "taw_op_rmsnorm_bwd": (C.c_int, [_i32, _i64, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _vp, _vp]),
+    "taw_op_rope": (C.c_int, [_i32, _i32, _i32, _i32, _i32, _vp, _i64, _vp, _i32, _vp]),
+    "taw_op_swiglu_fwd": (C.c_int, [_i32, _i64, _i32, _vp, _vp, _vp]),
+    "taw_op_swiglu_bwd": (C.c_int, [_i32, _i64, _i32, _vp, _vp, _vp, _vp]),
+    "taw_op_attn_fwd": (C.c_int, [_i32, _i32, _i32, _i32, _i32, _vp, _vp, _vp, _i32, _vp]),
+    "taw_op_attn_bwd": (C.c_int, [_i32, _i32, _i32, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _vp]),
+}
+EXPORTS = tuple(_SIGS)
+
+
+def load():
+    """Loads libtaw.so (built by paper_2511_09741_amd.build).  Raises if it is not there."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} not found: build it with `python -m paper_2511_09741_amd.build`; "
+                              "there is no fallback path")
+        lib = C.CDLL(LIB_PATH)
+        for name, (res, args) in _SIGS.items():
+            fn = getattr(lib, name)
+            fn.restype, fn.argtypes = res, args
+        _lib = lib
+    return _lib
+
+
+def _check(status: int):
+    if status != TAW_OK:
+        lib = load()
+        raise TawError(status, lib.taw_status_string(status).decode(), lib.taw_last_error().decode())
+
+
+def _p(t):
+    """Device (or host) pointer of a torch tensor, None -> NULL, int passes through."""
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    return t.data_ptr()
+
+
+def _stream(s):
+    if s is None:
+        return None
+    if isinstance(s, int):
+        return s
+    return s.cuda_stream
+
+
+def make_desc(dtype, B, S, H, n_heads, head_dim, I, rope_theta=10000.0, rms_eps=1e-6, flags=0) -> taw_layer_desc:
+    return taw_layer_desc(dtype, B, S, H, n_heads, head_dim, I, rope_theta, rms_eps, flags)
+
+
+def desc_from_config(cfg, flags=0) -> taw_layer_desc:
+    return make_desc(cfg.dtype, cfg.B, cfg.S, cfg.H, cfg.n_heads, cfg.head_dim, cfg.I, cfg.rope_theta, cfg.rms_eps, flags)
+
+
+# ----------------------------------------------------------------------------- taw.h
+def taw_layer_weight_layout(desc) -> dict:
+    out = taw_weight_layout()
+    _check(load().taw_layer_weight_layout(C.byref(desc), C.byref(out)))
+    return {f: int(getattr(out, f)) for f in LAYOUT_FIELDS}
+
+
+def taw_layer_ctx_bytes(desc) -> int:
+    return int(load().taw_layer_ctx_bytes(C.byref(desc)))
+
+
+def taw_layer_workspace_bytes(desc) -> int:
+    return int(load().taw_layer_workspace_bytes(C.byref(desc)))
+
+
+def taw_rope_table_init(desc, rope_table, stream=None):
+    _check(load().taw_rope_table_init(C.byref(desc), _p(rope_table), _stream(stream)))
+
+
+def taw_layer_fwd(desc, W_chunk, rope_table, x, y, ctx, workspace, workspace_bytes=None, stream=None):
+    if workspace_bytes is None:
+        workspace_bytes = workspace.numel() * workspace.element_size()
+    _check(load().taw_layer_fwd(C.byref(desc), _p(W_chunk), _p(rope_table), _p(x), _p(y), _p(ctx), _p(workspace),
+                                workspace_bytes, _stream(stream)))
+
+
+def taw_layer_bwd(desc, W_chunk, rope_table, x, dy, ctx, dx, G_shard, workspace, workspace_bytes=None, stream=None):
+    if workspace_bytes is None:
+        workspace_bytes = workspace.numel() * workspace.element_size()
+    _check(load().taw_layer_bwd(C.byref(desc), _p(W_chunk), _p(rope_table), _p(x), _p(dy), _p(ctx), _p(dx), _p(G_shard),
+                                _p(workspace), workspace_bytes, _stream(stream)))
+
+
+def taw_grad_accum(G_dst, g_src, src_dtype, n_elems, scale=1.0, stream=None):
+    _check(load().taw_grad_accum(_p(G_dst), _p(g_src), src_dtype, n_elems, scale, _stream(stream)))
+
+
+def taw_weight_stage(dst_buf, src_shard, nbytes, copy_stream=None, wait_event=None, ready_event=None):
+    we = wait_event.cuda_event if hasattr(wait_event, "cuda_event") else wait_event
+    re = ready_event.cuda_event if hasattr(ready_event, "cuda_event") else ready_event
+    _check(load().taw_weight_stage(_p(dst_buf), _p(src_shard), nbytes, _stream(copy_stream), we, re))
+
+
+def taw_status_string(status: int) -> str:
+    return load().taw_status_string(status).decode()
+
+
+def taw_last_error() -> str:
+    return load().taw_last_error().decode()
+
+
+# ----------------------------------------------------------------------------- taw_ops.h
+def taw_op_gemm(dtype, mode, M, N, K, A, lda, B, ldb, Cout, ldc, c_dtype, accumulate=0, R=None, ldr=0,
+                impl=TAW_IMPL_AUTO, stream=None):
+    _check(load().taw_op_gemm(dtype, mode, M, N, K, _p(A), lda, _p(B), ldb, _p(Cout), ldc, c_dtype, accumulate, _p(R), ldr,
+                              impl, _stream(stream)))
+
+
+def taw_op_rmsnorm_fwd(dtype, T, H, x, gamma, eps, out, r, stream=None):
+    _check(load().taw_op_rmsnorm_fwd(dtype, T, H, _p(x), _p(gamma), eps, _p(out), _p(r), _stream(stream)))
+
+
+def taw_op_rmsnorm_bwd_scratch_floats(H) -> int:
+    return int(load().taw_op_rmsnorm_bwd_scratch_floats(H))
+
+
+def taw_op_rmsnorm_bwd(dtype, T, H, dout, z, r, gamma, dres, dz, dgamma, accumulate, scratch, stream=None):
+    _check(load().taw_op_rmsnorm_bwd(dtype, T, H, _p(dout), _p(z), _p(r), _p(gamma), _p(dres), _p(dz), _p(dgamma), accumulate,
+                                     _p(scratch), _stream(stream)))
+
+
+def taw_op_rope(dtype, B, S, ncols, head_dim, z, ld, rope_table, inverse=0, stream=None):
+    _check(load().taw_op_rope(dtype, B, S, ncols, head_dim, _p(z), ld, _p(rope_table), inverse, _stream(stream)))
+
+
+def taw_op_swiglu_fwd(dtype, T, I, gu, a, stream=None):
+    _check(load().taw_op_swiglu_fwd(dtype, T, I, _p(gu), _p(a), _stream(stream)))
+
+
+def taw_op_swiglu_bwd(dtype, T, I, da, gu, dgu, stream=None):
+    _check(load().taw_op_swiglu_bwd(dtype, T, I, _p(da), _p(gu), _p(dgu), _stream(stream)))
+
+
+def taw_op_attn_fwd(dtype, B, S, n_heads, head_dim, qkv, o, lse, impl=TAW_IMPL_AUTO, stream=None):
+    _check(load().taw_op_attn_fwd(dtype, B, S, n_heads, head_dim, _p(qkv), _p(o), _p(lse), impl, _stream(stream)))
+
+
+def taw_op_attn_bwd(dtype, B, S, n_heads, head_dim, qkv, o, dO, lse, dqkv, scratch, impl=TAW_IMPL_AUTO, stream=None):
+    _check(load().taw_op_attn_bwd(dtype, B, S, n_heads, head_dim, _p(qkv), _p(o), _p(dO), _p(lse), _p(dqkv), _p(scratch), impl,
+                                  _stream(stream)))

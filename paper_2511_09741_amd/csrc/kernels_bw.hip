@@ -1,0 +1,489 @@
+// Bandwidth-bound kernels of the decoder layer: RMSNorm forward/backward, rotary embedding,
+// SwiGLU forward/backward, gradient-shard accumulation, the staging copy, the rotary table and
+// the attention-backward row dot product.  Each one streams its operands once with 16-byte
+// accesses per lane; reductions stay inside one wavefront (64 lanes) wherever a row fits.
+#include "dev_common.h"
+#include "taw_internal.h"
+
+namespace taw {
+
+// =============================================================================== RMSNorm forward
+// One wavefront per token row; the row stays packed in registers between the sum of squares
+// and the scaling, so x is read from HBM exactly once.
+template <typename T, int V, int MAXC>
+__global__ void __launch_bounds__(256) rmsnorm_fwd_kernel(const T* __restrict__ x, const T* __restrict__ gamma,
+                                                          T* __restrict__ out, float* __restrict__ r,
+                                                          int64_t rows, int H, float eps) {
+  const int lane = threadIdx.x & 63;
+  const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= rows) return;
+  const int nch = H / V;
+  const T* xr = x + row * (int64_t)H;
+  Vec<T, V> c[MAXC];
+  float ss = 0.f;
+#pragma unroll
+  for (int i = 0; i < MAXC; ++i) {
+    const int ci = i * 64 + lane;
+    if (ci < nch) {
+      c[i].load(xr + ci * V);
+#pragma unroll
+      for (int j = 0; j < V; ++j) { float v = c[i].get(j); ss += v * v; }
+    }
+  }
+  ss = wave_sum(ss);
+  const float rr = 1.0f / sqrtf(ss / (float)H + eps);
+  if (lane == 0) r[row] = rr;
+  T* orow = out + row * (int64_t)H;
+#pragma unroll
+  for (int i = 0; i < MAXC; ++i) {
+    const int ci = i * 64 + lane;
+    if (ci < nch) {
+      Vec<T, V> g, o;
+      g.load(gamma + ci * V);
+#pragma unroll
+      for (int j = 0; j < V; ++j) o.set(j, c[i].get(j) * rr * g.get(j));
+      o.store(orow + ci * V);
+    }
+  }
+}
+
+// =============================================================================== RMSNorm backward
+// c = dout*gamma;  dz = r c - z r^3 mean(c z) (+ dres);  dgamma_i = sum_t dout[t,i] z[t,i] r_t.
+// A wavefront walks rows with a grid stride and keeps its share of the dgamma column sums in
+// registers; the four wavefronts of a workgroup are then summed in a fixed order through LDS and
+// written as one partial row, which colsum_kernel reduces.  No atomics: results are reproducible.
+template <typename T, int V, int MAXC>
+__global__ void __launch_bounds__(256) rmsnorm_bwd_kernel(const T* __restrict__ dout, const T* __restrict__ z,
+                                                          const float* __restrict__ r, const T* __restrict__ gamma,
+                                                          const T* __restrict__ dres, T* __restrict__ dz,
+                                                          float* __restrict__ partials, int64_t rows, int H) {
+  extern __shared__ float lds_cols[];  // [H]
+  const int lane = threadIdx.x & 63;
+  const int wave = threadIdx.x >> 6;
+  const int nch = H / V;
+  float acc[MAXC][V];
+  Vec<T, V> g[MAXC];
+#pragma unroll
+  for (int i = 0; i < MAXC; ++i) {
+    const int ci = i * 64 + lane;
+    if (ci < nch) g[i].load(gamma + ci * V);
+#pragma unroll
+    for (int j = 0; j < V; ++j) acc[i][j] = 0.f;
+  }
+  const float invH = 1.0f / (float)H;
+  for (int64_t row = (int64_t)blockIdx.x * 4 + wave; row < rows; row += (int64_t)gridDim.x * 4) {
+    const int64_t base = row * (int64_t)H;
+    Vec<T, V> zc[MAXC], dc[MAXC];
+    float dot = 0.f;
+#pragma unroll
+    for (int i = 0; i < MAXC; ++i) {
+      const int ci = i * 64 + lane;
+      if (ci < nch) {
+        zc[i].load(z + base + ci * V);
+        dc[i].load(dout + base + ci * V);
+      }
+    }
+    const float rr = r[row];
+#pragma unroll
+    for (int i = 0; i < MAXC; ++i) {
+      const int ci = i * 64 + lane;
+      if (ci < nch) {
+#pragma unroll
+        for (int j = 0; j < V; ++j) {
+          const float zz = zc[i].get(j), dd = dc[i].get(j);
+          dot += dd * g[i].get(j) * zz;
+          acc[i][j] += dd * zz * rr;
+        }
+      }
+    }
+    dot = wave_sum(dot);
+    const float coef = rr * rr * rr * dot * invH;
+#pragma unroll
+    for (int i = 0; i < MAXC; ++i) {
+      const int ci = i * 64 + lane;
+      if (ci < nch) {
+        Vec<T, V> o, res;
+        if (dres) res.load(dres + base + ci * V);
+#pragma unroll
+        for (int j = 0; j < V; ++j) {
+          float v = rr * dc[i].get(j) * g[i].get(j) - zc[i].get(j) * coef;
+          if (dres) v += res.get(j);
+          o.set(j, v);
+        }
+        o.store(dz + base + ci * V);
+      }
+    }
+  }
+  // fixed-order sum of the four wavefronts' column sums
+  for (int w = 0; w < 4; ++w) {
+    if (wave == w) {
+#pragma unroll
+      for (int i = 0; i < MAXC; ++i) {
+        const int ci = i * 64 + lane;
+        if (ci < nch) {
+#pragma unroll
+          for (int j = 0; j < V; ++j) {
+            if (w == 0) lds_cols[ci * V + j] = acc[i][j];
+            else lds_cols[ci * V + j] += acc[i][j];
+          }
+        }
+      }
+    }
+    __syncthreads();
+  }
+  float* prow = partials + (int64_t)blockIdx.x * H;
+  for (int c = threadIdx.x; c < H; c += 256) prow[c] = lds_cols[c];
+}
+
+// out[c] (=|+=) sum_p partials[p][c], p ascending
+__global__ void __launch_bounds__(256) colsum_kernel(const float* __restrict__ partials, int np, int H,
+                                                     float* __restrict__ out, int accumulate) {
+  const int c = blockIdx.x * 256 + threadIdx.x;
+  if (c >= H) return;
+  float s = 0.f;
+  for (int p = 0; p < np; ++p) s += partials[(int64_t)p * H + c];
+  out[c] = accumulate ? out[c] + s : s;
+}
+
+// =============================================================================== rotary table
+// table[p][i] = (cos, sin)(p * theta^(-2i/d)), evaluated in fp64 (fp32 sin/cos lose accuracy at
+// arguments of order 3e4), stored fp32.
+__global__ void __launch_bounds__(256) rope_table_kernel(float* __restrict__ table, int S, int half, double theta, int d) {
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= (int64_t)S * half) return;
+  const int p = (int)(idx / half), i = (int)(idx % half);
+  const double inv_freq = exp(-(2.0 * (double)i / (double)d) * log(theta));
+  const double ang = (double)p * inv_freq;
+  table[2 * idx] = (float)cos(ang);
+  table[2 * idx + 1] = (float)sin(ang);
+}
+
+// =============================================================================== rotary embedding
+// In place on columns [0, ncols) of z[B*S, ld].  Adjacent pairs (2i, 2i+1) of every head:
+// (a, b) -> (a cos - b sin, a sin + b cos); inverse rotates by the negative angle.
+template <typename T, int V>
+__global__ void __launch_bounds__(256) rope_kernel(T* __restrict__ z, int64_t ld, int64_t rows, int S, int ncols,
+                                                   int d, const float* __restrict__ table, int inverse) {
+  const int cpr = ncols / V;  // chunks per row
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= rows * cpr) return;
+  const int64_t row = idx / cpr;
+  const int col = (int)(idx % cpr) * V;
+  const int p = (int)(row % S);
+  T* ptr = z + row * ld + col;
+  Vec<T, V> v;
+  v.load(ptr);
+  const int half = d / 2;
+  const float* tb = table + ((int64_t)p * half + (col % d) / 2) * 2;
+  Vec<T, V> o;
+#pragma unroll
+  for (int j = 0; j < V; j += 2) {
+    const float c = tb[j], s = inverse ? -tb[j + 1] : tb[j + 1];
+    const float a = v.get(j), b = v.get(j + 1);
+    o.set(j, a * c - b * s);
+    o.set(j + 1, a * s + b * c);
+  }
+  o.store(ptr);
+}
+
+// scalar-pair variant for head dims that are not a multiple of the vector width
+template <typename T>
+__global__ void __launch_bounds__(256) rope_pair_kernel(T* __restrict__ z, int64_t ld, int64_t rows, int S, int ncols,
+                                                        int d, const float* __restrict__ table, int inverse) {
+  const int ppr = ncols / 2;
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= rows * ppr) return;
+  const int64_t row = idx / ppr;
+  const int col = (int)(idx % ppr) * 2;
+  const int p = (int)(row % S);
+  const float* tb = table + ((int64_t)p * (d / 2) + (col % d) / 2) * 2;
+  const float c = tb[0], s = inverse ? -tb[1] : tb[1];
+  T* ptr = z + row * ld + col;
+  const float a = (float)ptr[0], b = (float)ptr[1];
+  ptr[0] = (T)(a * c - b * s);
+  ptr[1] = (T)(a * s + b * c);
+}
+
+// =============================================================================== SwiGLU
+// gu = [gate | up] per row ([T, 2I]);  a = gate * sigmoid(gate) * up.
+template <typename T, int V>
+__global__ void __launch_bounds__(256) swiglu_fwd_kernel(const T* __restrict__ gu, T* __restrict__ a, int64_t rows, int I) {
+  const int cpr = I / V;
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= rows * cpr) return;
+  const int64_t row = idx / cpr;
+  const int col = (int)(idx % cpr) * V;
+  Vec<T, V> g, u, o;
+  g.load(gu + row * 2 * (int64_t)I + col);
+  u.load(gu + row * 2 * (int64_t)I + I + col);
+#pragma unroll
+  for (int j = 0; j < V; ++j) {
+    const float gg = g.get(j);
+    const float sig = 1.0f / (1.0f + __expf(-gg));
+    o.set(j, gg * sig * u.get(j));
+  }
+  o.store(a + row * (int64_t)I + col);
+}
+
+// dg = da u sig (1 + g (1 - sig));  du = da g sig
+template <typename T, int V>
+__global__ void __launch_bounds__(256) swiglu_bwd_kernel(const T* __restrict__ da, const T* __restrict__ gu,
+                                                         T* __restrict__ dgu, int64_t rows, int I) {
+  const int cpr = I / V;
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= rows * cpr) return;
+  const int64_t row = idx / cpr;
+  const int col = (int)(idx % cpr) * V;
+  Vec<T, V> g, u, d, og, ou;
+  g.load(gu + row * 2 * (int64_t)I + col);
+  u.load(gu + row * 2 * (int64_t)I + I + col);
+  d.load(da + row * (int64_t)I + col);
+#pragma unroll
+  for (int j = 0; j < V; ++j) {
+    const float gg = g.get(j), dd = d.get(j);
+    const float sig = 1.0f / (1.0f + __expf(-gg));
+    og.set(j, dd * u.get(j) * sig * (1.0f + gg * (1.0f - sig)));
+    ou.set(j, dd * gg * sig);
+  }
+  og.store(dgu + row * 2 * (int64_t)I + col);
+  ou.store(dgu + row * 2 * (int64_t)I + I + col);
+}
+
+// =============================================================================== gradient accumulation
+// G[i] += scale * g[i]; 16 bytes of G per lane per step, grid-stride.
+template <typename TS>
+__global__ void __launch_bounds__(256) grad_accum_kernel(float* __restrict__ G, const TS* __restrict__ g, size_t n, float scale) {
+  const size_t nvec = n / 4;
+  const size_t stride = (size_t)gridDim.x * 256;
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < nvec; i += stride) {
+    f32x4_t acc = *reinterpret_cast<const f32x4_t*>(G + 4 * i);
+    if constexpr (sizeof(TS) == 4) {
+      const f32x4_t s = *reinterpret_cast<const f32x4_t*>(g + 4 * i);
+      acc += s * scale;
+    } else {
+      const bf16x4_t s = *reinterpret_cast<const bf16x4_t*>(g + 4 * i);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) acc[j] += (float)s[j] * scale;
+    }
+    *reinterpret_cast<f32x4_t*>(G + 4 * i) = acc;
+  }
+  // tail (n not a multiple of 4)
+  if (blockIdx.x == 0 && threadIdx.x < (n & 3)) {
+    const size_t i = nvec * 4 + threadIdx.x;
+    G[i] += (float)g[i] * scale;
+  }
+}
+
+// =============================================================================== staging copy
+// HBM-to-HBM copy of a weight chunk.  A modest grid on purpose: it runs beside the layer's
+// compute kernels on another stream and should take few compute units away from them.
+__global__ void __launch_bounds__(256) stage_copy_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, size_t nvec) {
+  const size_t stride = (size_t)gridDim.x * 256;
+  size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  for (; i + 3 * stride < nvec; i += 4 * stride) {
+    const uint4 a = src[i], b = src[i + stride], c = src[i + 2 * stride], d = src[i + 3 * stride];
+    dst[i] = a; dst[i + stride] = b; dst[i + 2 * stride] = c; dst[i + 3 * stride] = d;
+  }
+  for (; i < nvec; i += stride) dst[i] = src[i];
+}
+
+// =============================================================================== attention row dot
+// D[b,h,t] = sum_i do[t, h*d+i] * o[t, h*d+i]; one thread group of d/V lanes per (t, h).
+template <typename T, int V>
+__global__ void __launch_bounds__(256) attn_rowdot_kernel(const T* __restrict__ o, int64_t ld_o, const T* __restrict__ dO,
+                                                          int64_t ld_do, float* __restrict__ D, int B, int S, int nh, int d) {
+  // one thread per (row, head): small d/V (16 lanes x 8 for d=128) would need a segmented
+  // reduction; a single thread reading d contiguous elements keeps 16-byte accesses instead.
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  const int64_t rows = (int64_t)B * S;
+  if (idx >= rows * nh) return;
+  // consecutive threads take consecutive rows of one head so the D stores are coalesced
+  const int64_t t = idx % rows;
+  const int h = (int)(idx / rows);
+  const T* po = o + t * ld_o + (int64_t)h * d;
+  const T* pd = dO + t * ld_do + (int64_t)h * d;
+  float s = 0.f;
+  for (int c = 0; c < d; c += V) {
+    Vec<T, V> a, b;
+    a.load(po + c);
+    b.load(pd + c);
+#pragma unroll
+    for (int j = 0; j < V; ++j) s += a.get(j) * b.get(j);
+  }
+  const int b_ = (int)(t / S), p = (int)(t % S);
+  D[((int64_t)b_ * nh + h) * S + p] = s;
+}
+
+// =============================================================================== launchers
+static inline int last_err() { return (int)hipGetLastError(); }
+
+template <typename T> static constexpr int vw() { return VecWidth<T>::value; }
+
+bool rmsnorm_supported(int dtype, int H) {
+  const int V = dtype == DT_BF16 ? 8 : 4;
+  if (H <= 0) return false;
+  if (H % V == 0) return H / V <= 64 * 16;
+  return H <= 64 * 16;
+}
+
+template <typename T, int V>
+static int rmsnorm_fwd_dispatch(int64_t T_, int H, const T* x, const T* g, float eps, T* out, float* r, hipStream_t st) {
+  const int nch = H / V;
+  const unsigned grid = (unsigned)((T_ + 3) / 4);
+#define TAW_RN_FWD(MAXC) hipLaunchKernelGGL((rmsnorm_fwd_kernel<T, V, MAXC>), dim3(grid), dim3(256), 0, st, x, g, out, r, T_, H, eps)
+  if (nch <= 64) TAW_RN_FWD(1);
+  else if (nch <= 128) TAW_RN_FWD(2);
+  else if (nch <= 256) TAW_RN_FWD(4);
+  else if (nch <= 512) TAW_RN_FWD(8);
+  else TAW_RN_FWD(16);
+#undef TAW_RN_FWD
+  return last_err();
+}
+
+int launch_rmsnorm_fwd(int dtype, int64_t T_, int H, const void* x, const void* gamma, float eps, void* out,
+                       float* r, hipStream_t st) {
+  if (T_ == 0) return 0;
+  if (dtype == DT_BF16) {
+    if (H % 8 == 0) return rmsnorm_fwd_dispatch<bf16_t, 8>(T_, H, (const bf16_t*)x, (const bf16_t*)gamma, eps, (bf16_t*)out, r, st);
+    return rmsnorm_fwd_dispatch<bf16_t, 1>(T_, H, (const bf16_t*)x, (const bf16_t*)gamma, eps, (bf16_t*)out, r, st);
+  }
+  if (H % 4 == 0) return rmsnorm_fwd_dispatch<float, 4>(T_, H, (const float*)x, (const float*)gamma, eps, (float*)out, r, st);
+  return rmsnorm_fwd_dispatch<float, 1>(T_, H, (const float*)x, (const float*)gamma, eps, (float*)out, r, st);
+}
+
+static constexpr int kNormBwdGrid = 512;
+int rmsnorm_bwd_partial_rows() { return kNormBwdGrid; }
+
+template <typename T, int V>
+static int rmsnorm_bwd_dispatch(int64_t T_, int H, const T* dout, const T* z, const float* r, const T* g,
+                                const T* dres, T* dz, float* dgamma, int accumulate, float* partials, hipStream_t st) {
+  const int nch = H / V;
+  int grid = (int)((T_ + 3) / 4);
+  if (grid > kNormBwdGrid) grid = kNormBwdGrid;
+  const size_t lds = (size_t)H * sizeof(float);
+#define TAW_RN_BWD(MAXC) hipLaunchKernelGGL((rmsnorm_bwd_kernel<T, V, MAXC>), dim3(grid), dim3(256), lds, st, dout, z, r, g, dres, dz, partials, T_, H)
+  if (nch <= 64) TAW_RN_BWD(1);
+  else if (nch <= 128) TAW_RN_BWD(2);
+  else if (nch <= 256) TAW_RN_BWD(4);
+  else if (nch <= 512) TAW_RN_BWD(8);
+  else TAW_RN_BWD(16);
+#undef TAW_RN_BWD
+  int e = last_err();
+  if (e) return e;
+  hipLaunchKernelGGL(colsum_kernel, dim3((H + 255) / 256), dim3(256), 0, st, partials, grid, H, dgamma, accumulate);
+  return last_err();
+}
+
+int launch_rmsnorm_bwd(int dtype, int64_t T_, int H, const void* dout, const void* z, const float* r,
+                       const void* gamma, const void* dres, void* dz, float* dgamma, int accumulate,
+                       float* partials, hipStream_t st) {
+  if (T_ == 0) return 0;
+  if (dtype == DT_BF16) {
+    if (H % 8 == 0)
+      return rmsnorm_bwd_dispatch<bf16_t, 8>(T_, H, (const bf16_t*)dout, (const bf16_t*)z, r, (const bf16_t*)gamma,
+                                             (const bf16_t*)dres, (bf16_t*)dz, dgamma, accumulate, partials, st);
+    return rmsnorm_bwd_dispatch<bf16_t, 1>(T_, H, (const bf16_t*)dout, (const bf16_t*)z, r, (const bf16_t*)gamma,
+                                           (const bf16_t*)dres, (bf16_t*)dz, dgamma, accumulate, partials, st);
+  }
+  if (H % 4 == 0)
+    return rmsnorm_bwd_dispatch<float, 4>(T_, H, (const float*)dout, (const float*)z, r, (const float*)gamma,
+                                          (const float*)dres, (float*)dz, dgamma, accumulate, partials, st);
+  return rmsnorm_bwd_dispatch<float, 1>(T_, H, (const float*)dout, (const float*)z, r, (const float*)gamma,
+                                        (const float*)dres, (float*)dz, dgamma, accumulate, partials, st);
+}
+
+int launch_rope_table(int S, int head_dim, double theta, float* table, hipStream_t st) {
+  const int half = head_dim / 2;
+  const int64_t n = (int64_t)S * half;
+  if (n == 0) return 0;
+  hipLaunchKernelGGL(rope_table_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, table, S, half, theta, head_dim);
+  return last_err();
+}
+
+template <typename T>
+static int rope_dispatch(int B, int S, int ncols, int d, T* z, int64_t ld, const float* table, int inverse, hipStream_t st) {
+  constexpr int V = VecWidth<T>::value;
+  const int64_t rows = (int64_t)B * S;
+  if (rows == 0 || ncols == 0) return 0;
+  if (d % V == 0 && ld % V == 0) {
+    const int64_t n = rows * (ncols / V);
+    hipLaunchKernelGGL((rope_kernel<T, V>), dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, z, ld, rows, S, ncols, d, table, inverse);
+  } else {
+    const int64_t n = rows * (ncols / 2);
+    hipLaunchKernelGGL((rope_pair_kernel<T>), dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, z, ld, rows, S, ncols, d, table, inverse);
+  }
+  return last_err();
+}
+
+int launch_rope(int dtype, int B, int S, int ncols, int head_dim, void* z, int64_t ld, const float* table,
+                int inverse, hipStream_t st) {
+  if (dtype == DT_BF16) return rope_dispatch<bf16_t>(B, S, ncols, head_dim, (bf16_t*)z, ld, table, inverse, st);
+  return rope_dispatch<float>(B, S, ncols, head_dim, (float*)z, ld, table, inverse, st);
+}
+
+template <typename T>
+static int swiglu_dispatch(bool bwd, int64_t T_, int I, const T* da, const T* gu, T* out, hipStream_t st) {
+  constexpr int VW = VecWidth<T>::value;
+  if (T_ == 0 || I == 0) return 0;
+  if (I % VW == 0) {
+    const int64_t n = T_ * (I / VW);
+    const unsigned grid = (unsigned)((n + 255) / 256);
+    if (bwd) hipLaunchKernelGGL((swiglu_bwd_kernel<T, VW>), dim3(grid), dim3(256), 0, st, da, gu, out, T_, I);
+    else hipLaunchKernelGGL((swiglu_fwd_kernel<T, VW>), dim3(grid), dim3(256), 0, st, gu, out, T_, I);
+  } else {
+    const int64_t n = T_ * I;
+    const unsigned grid = (unsigned)((n + 255) / 256);
+    if (bwd) hipLaunchKernelGGL((swiglu_bwd_kernel<T, 1>), dim3(grid), dim3(256), 0, st, da, gu, out, T_, I);
+    else hipLaunchKernelGGL((swiglu_fwd_kernel<T, 1>), dim3(grid), dim3(256), 0, st, gu, out, T_, I);
+  }
+  return last_err();
+}
+
+int launch_swiglu_fwd(int dtype, int64_t T_, int I, const void* gu, void* a, hipStream_t st) {
+  if (dtype == DT_BF16) return swiglu_dispatch<bf16_t>(false, T_, I, nullptr, (const bf16_t*)gu, (bf16_t*)a, st);
+  return swiglu_dispatch<float>(false, T_, I, nullptr, (const float*)gu, (float*)a, st);
+}
+int launch_swiglu_bwd(int dtype, int64_t T_, int I, const void* da, const void* gu, void* dgu, hipStream_t st) {
+  if (dtype == DT_BF16) return swiglu_dispatch<bf16_t>(true, T_, I, (const bf16_t*)da, (const bf16_t*)gu, (bf16_t*)dgu, st);
+  return swiglu_dispatch<float>(true, T_, I, (const float*)da, (const float*)gu, (float*)dgu, st);
+}
+
+int launch_grad_accum(float* G, const void* g, int src_dtype, size_t n, float scale, hipStream_t st) {
+  if (n == 0) return 0;
+  size_t want = (n / 4 + 255) / 256;
+  if (want == 0) want = 1;
+  const unsigned grid = (unsigned)(want > 8192 ? 8192 : want);
+  if (src_dtype == DT_BF16) hipLaunchKernelGGL((grad_accum_kernel<bf16_t>), dim3(grid), dim3(256), 0, st, G, (const bf16_t*)g, n, scale);
+  else hipLaunchKernelGGL((grad_accum_kernel<float>), dim3(grid), dim3(256), 0, st, G, (const float*)g, n, scale);
+  return last_err();
+}
+
+int launch_stage_copy(void* dst, const void* src, size_t bytes, hipStream_t st) {
+  const size_t nvec = bytes / 16;
+  if (nvec == 0) return 0;
+  size_t want = (nvec + 255) / 256;
+  const unsigned grid = (unsigned)(want > 256 ? 256 : want);
+  hipLaunchKernelGGL(stage_copy_kernel, dim3(grid), dim3(256), 0, st, (const uint4*)src, (uint4*)dst, nvec);
+  return last_err();
+}
+
+int launch_attn_rowdot(int dtype, int B, int S, int nh, int d, const void* o, int64_t ld_o, const void* dO,
+                       int64_t ld_do, float* D, hipStream_t st) {
+  const int64_t n = (int64_t)B * S * nh;
+  if (n == 0) return 0;
+  const unsigned grid = (unsigned)((n + 255) / 256);
+  if (dtype == DT_BF16) {
+    if (d % 8 == 0 && ld_o % 8 == 0 && ld_do % 8 == 0)
+      hipLaunchKernelGGL((attn_rowdot_kernel<bf16_t, 8>), dim3(grid), dim3(256), 0, st, (const bf16_t*)o, ld_o, (const bf16_t*)dO, ld_do, D, B, S, nh, d);
+    else
+      hipLaunchKernelGGL((attn_rowdot_kernel<bf16_t, 1>), dim3(grid), dim3(256), 0, st, (const bf16_t*)o, ld_o, (const bf16_t*)dO, ld_do, D, B, S, nh, d);
+  } else {
+    if (d % 4 == 0 && ld_o % 4 == 0 && ld_do % 4 == 0)
+      hipLaunchKernelGGL((attn_rowdot_kernel<float, 4>), dim3(grid), dim3(256), 0, st, (const float*)o, ld_o, (const float*)dO, ld_do, D, B, S, nh, d);
+    else
+      hipLaunchKernelGGL((attn_rowdot_kernel<float, 1>), dim3(grid), dim3(256), 0, st, (const float*)o, ld_o, (const float*)dO, ld_do, D, B, S, nh, d);
+  }
+  return last_err();
+}
+
+}  // namespace taw

@@ -1,0 +1,65 @@
+// Internal launch interface between the C-ABI front end (taw_api.cpp) and the kernel files.
+// Every launcher validates nothing (the front end did), enqueues on `st`, and returns the
+// hipError_t of its last launch as an int (0 = success).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace taw {
+
+enum { DT_F32 = 0, DT_BF16 = 1 };
+enum { GEMM_NT = 0, GEMM_NN = 1, GEMM_TN = 2 };
+
+inline size_t dt_size(int dt) { return dt == DT_BF16 ? 2 : 4; }
+
+// ---- bandwidth-bound kernels (kernels_bw.hip) ------------------------------------------------
+// Largest H the RMSNorm kernels hold in registers: H * sizeof(elem) <= 16 KiB when H is a multiple
+// of the 16-byte vector width, else H <= 1024.
+bool rmsnorm_supported(int dtype, int H);
+int launch_rmsnorm_fwd(int dtype, int64_t T, int H, const void* x, const void* gamma, float eps,
+                       void* out, float* r, hipStream_t st);
+// number of fp32 partial-sum rows (each H wide) the backward needs as scratch
+int rmsnorm_bwd_partial_rows();
+// dz = (dres ? dres : 0) + rmsnorm_bwd(dout);  dgamma (=|+=) column sums
+int launch_rmsnorm_bwd(int dtype, int64_t T, int H, const void* dout, const void* z, const float* r,
+                       const void* gamma, const void* dres, void* dz, float* dgamma, int accumulate,
+                       float* partials, hipStream_t st);
+int launch_rope_table(int S, int head_dim, double theta, float* table, hipStream_t st);
+// rotates columns [0, ncols) of the [B*S, ld] matrix z in place; column j belongs to pair (j % d)/2
+int launch_rope(int dtype, int B, int S, int ncols, int head_dim, void* z, int64_t ld,
+                const float* table, int inverse, hipStream_t st);
+int launch_swiglu_fwd(int dtype, int64_t T, int I, const void* gu, void* a, hipStream_t st);
+int launch_swiglu_bwd(int dtype, int64_t T, int I, const void* da, const void* gu, void* dgu,
+                      hipStream_t st);
+int launch_grad_accum(float* G, const void* g, int src_dtype, size_t n, float scale, hipStream_t st);
+int launch_stage_copy(void* dst, const void* src, size_t bytes, hipStream_t st);
+// D[b, h, t] = sum_i do[t, h*d + i] * o[t, h*d + i]   (o, do are [B*S, ld_o] / [B*S, ld_do])
+int launch_attn_rowdot(int dtype, int B, int S, int nh, int d, const void* o, int64_t ld_o,
+                       const void* dO, int64_t ld_do, float* D, hipStream_t st);
+
+// ---- generic (any shape, fp32 or bf16 storage, fp32 arithmetic) kernels (kernels_generic.hip) --
+// C[M,N] (=|+=) op(A) op(B) (+ R).  mode NT: A[M,K], B[N,K];  NN: A[M,K], B[K,N];  TN: A[K,M], B[K,N].
+// c_dtype is the storage type of C and R (in dtype or fp32); accumulate adds into C.
+int launch_gemm_generic(int dtype, int mode, int64_t M, int64_t N, int64_t K, const void* A, int64_t lda,
+                        const void* B, int64_t ldb, void* C, int64_t ldc, int c_dtype, int accumulate,
+                        const void* R, int64_t ldr, hipStream_t st);
+// qkv: [B*S, 3H] (q | k | v, head-major);  o: [B*S, H];  lse: [B, nh, S] natural-log-sum-exp of the scaled scores
+bool attn_generic_supported(int S, int d);
+int launch_attn_fwd_generic(int dtype, int B, int S, int nh, int d, const void* qkv, void* o, float* lse,
+                            hipStream_t st);
+int launch_attn_bwd_generic(int dtype, int B, int S, int nh, int d, const void* qkv, const void* dO,
+                            const float* lse, const float* D, void* dqkv, hipStream_t st);
+
+// ---- MFMA bf16 kernels (gemm_mfma.hip, attn_mfma.hip) -----------------------------------------
+bool gemm_mfma_supported(int dtype, int mode, int64_t M, int64_t N, int64_t K, int64_t lda, int64_t ldb,
+                         int64_t ldc, int c_dtype, int64_t ldr);
+int launch_gemm_mfma(int mode, int64_t M, int64_t N, int64_t K, const void* A, int64_t lda, const void* B,
+                     int64_t ldb, void* C, int64_t ldc, int c_dtype, int accumulate, const void* R,
+                     int64_t ldr, hipStream_t st);
+bool attn_mfma_supported(int dtype, int S, int d);
+int launch_attn_fwd_mfma(int B, int S, int nh, const void* qkv, void* o, float* lse, hipStream_t st);
+int launch_attn_bwd_mfma(int B, int S, int nh, const void* qkv, const void* dO, const float* lse,
+                         const float* D, void* dqkv, hipStream_t st);
+
+}  // namespace taw

@@ -1,0 +1,166 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol the
+headers declare, computes the chunk layout, and rejects bad arguments before any launch."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+import paper_2511_09741_amd.binding as taw
+from paper_2511_09741_amd import inputs as I
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(taw.LIB_PATH):
+        from paper_2511_09741_amd.build import build
+        build()
+    return taw.load()
+
+
+def declared_functions():
+    names = []
+    for h in ("taw.h", "taw_ops.h"):
+        src = open(os.path.join(ROOT, "include", h)).read()
+        src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+        names += re.findall(r"\b(taw_[a-z0-9_]+)\s*\(", src)
+    return sorted(set(names))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = declared_functions()
+    assert len(names) == 19
+    for n in names:
+        assert hasattr(lib, n), f"{n} declared in include/ but not exported"
+    assert set(names) == set(taw.EXPORTS)
+
+
+def test_status_strings(lib):
+    assert taw.taw_status_string(0) == "TAW_OK"
+    assert taw.taw_status_string(-5) == "TAW_ERR_WORKSPACE"
+    assert taw.taw_status_string(-99) == "TAW_ERR_UNKNOWN"
+
+
+def test_weight_layout_matches_the_papers_parameter_count(lib):
+    """A layer holds 4H^2 + 3HI matrix parameters (about 12 H^2, Theoretical Analysis) + 2H gains."""
+    d = taw.desc_from_config(I.CONFIGS["C2"])
+    L = taw.taw_layer_weight_layout(d)
+    H, I_ = 4096, 11008
+    assert L["total_elems"] == 4 * H * H + 3 * H * I_ + 2 * H == 202_383_360
+    assert abs(L["total_elems"] / (12 * H * H) - 1) < 0.01
+    assert [L[k] for k in taw.LAYOUT_FIELDS[:-1]] == sorted(L[k] for k in taw.LAYOUT_FIELDS[:-1])
+    assert L["w_qkv"] == H and L["w_o"] == H + 3 * H * H
+    # tiny config: sub-tensors are padded to 128-element boundaries and do not overlap
+    c1 = I.CONFIGS["C1"]
+    L1 = taw.taw_layer_weight_layout(taw.desc_from_config(c1))
+    sizes = {"gamma_attn": 64, "w_qkv": 192 * 64, "w_o": 64 * 64, "gamma_mlp": 64, "w_gate_up": 352 * 64, "w_down": 64 * 176}
+    end = 0
+    for k in taw.LAYOUT_FIELDS[:-1]:
+        assert L1[k] % 128 == 0 and L1[k] >= end
+        end = L1[k] + sizes[k]
+    assert L1["total_elems"] >= end and L1["total_elems"] % 128 == 0
+    assert sum(sizes.values()) == 50_304
+
+
+def test_ctx_and_workspace_sizes(lib):
+    d = taw.desc_from_config(I.CONFIGS["C3"])
+    ctx, ws = taw.taw_layer_ctx_bytes(d), taw.taw_layer_workspace_bytes(d)
+    T, H, I_ = 32768, 4096, 11008
+    assert ctx >= 2 * T * (7 * H + 3 * I_) and ctx < 5 * 2**30
+    assert ws >= 2 * T * (7 * H + 3 * I_) and ws < 5 * 2**30
+    bad = taw.make_desc(1, 1, 128, 100, 3, 32, 64)
+    assert taw.taw_layer_ctx_bytes(bad) == 0 and taw.taw_layer_workspace_bytes(bad) == 0
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(H=100), taw.TAW_ERR_SHAPE), (dict(S=0), taw.TAW_ERR_SHAPE), (dict(B=-1), taw.TAW_ERR_SHAPE),
+    (dict(dtype=7), taw.TAW_ERR_DTYPE), (dict(head_dim=15, n_heads=4, H=60), taw.TAW_ERR_SHAPE),
+    (dict(flags=8), taw.TAW_ERR_SHAPE), (dict(rope_theta=0.0), taw.TAW_ERR_SHAPE),
+])
+def test_bad_descriptors_are_rejected(lib, kw, code):
+    base = dict(dtype=0, B=1, S=128, H=64, n_heads=4, head_dim=16, I=176)
+    base.update(kw)
+    d = taw.make_desc(**base)
+    with pytest.raises(taw.TawError) as e:
+        taw.taw_layer_weight_layout(d)
+    assert e.value.status == code
+    assert taw.taw_last_error()
+
+
+def test_layer_calls_validate_before_launching(lib):
+    d = taw.desc_from_config(I.CONFIGS["C1"])
+    ws = taw.taw_layer_workspace_bytes(d)
+    ok = 0x10000  # a 16-byte aligned fake address; every call below must fail before using it
+    with pytest.raises(taw.TawError) as e:
+        taw.taw_layer_fwd(d, None, ok, ok, ok + 4096, ok, ok, ws)
+    assert e.value.status == taw.TAW_ERR_NULL
+    with pytest.raises(taw.TawError) as e:
+        taw.taw_layer_fwd(d, ok, ok, ok + 4, ok + 4096, ok, ok, ws)
+    assert e.value.status == taw.TAW_ERR_ALIGN
+    with pytest.raises(taw.TawError) as e:
+        taw.taw_layer_fwd(d, ok, ok, ok, ok + 4096, ok, ok, ws - 1)
+    assert e.value.status == taw.TAW_ERR_WORKSPACE
+    with pytest.raises(taw.TawError) as e:
+        taw.taw_layer_fwd(d, ok, ok, ok, ok, ok, ok, ws)
+    assert e.value.status == taw.TAW_ERR_SHAPE           # y aliases x
+    with pytest.raises(taw.TawError) as e:
+        taw.taw_layer_bwd(d, ok, ok, ok, ok + 4096, ok, ok + 8192, None, ok, ws)
+    assert e.value.status == taw.TAW_ERR_NULL
+    with pytest.raises(taw.TawError) as e:
+        taw.taw_layer_bwd(d, ok, ok, ok, ok + 4096, ok, ok + 4096, ok, ok, ws)
+    assert e.value.status == taw.TAW_ERR_SHAPE           # dx aliases dy
+    big = taw.make_desc(0, 1, 8192, 64, 4, 16, 176)       # fp32 has no MFMA attention; generic takes S <= 4096
+    with pytest.raises(taw.TawError) as e:
+        taw.taw_layer_fwd(big, ok, ok, ok, ok + 4096, ok, ok, taw.taw_layer_workspace_bytes(big))
+    assert e.value.status == taw.TAW_ERR_UNSUPPORTED
+
+
+def test_grad_accum_and_stage_validation(lib):
+    ok = 0x10000
+    taw.taw_grad_accum(None, None, taw.TAW_F32, 0)          # n = 0 is a no-op
+    with pytest.raises(taw.TawError) as e:
+        taw.taw_grad_accum(ok, ok + 8, taw.TAW_F32, 16)
+    assert e.value.status == taw.TAW_ERR_ALIGN
+    with pytest.raises(taw.TawError) as e:
+        taw.taw_grad_accum(ok, ok + 16, taw.TAW_F32, 16)
+    assert e.value.status == taw.TAW_ERR_SHAPE           # overlap
+    with pytest.raises(taw.TawError) as e:
+        taw.taw_grad_accum(ok, ok + 4096, 5, 16)
+    assert e.value.status == taw.TAW_ERR_DTYPE
+    with pytest.raises(taw.TawError) as e:
+        taw.taw_weight_stage(ok, ok + 4096, 24)
+    assert e.value.status == taw.TAW_ERR_SHAPE           # not a multiple of 16
+    with pytest.raises(taw.TawError) as e:
+        taw.taw_weight_stage(None, ok, 32)
+    assert e.value.status == taw.TAW_ERR_NULL
+    with pytest.raises(taw.TawError) as e:
+        taw.taw_weight_stage(ok, ok + 16, 32)
+    assert e.value.status == taw.TAW_ERR_SHAPE           # overlap
+
+
+def test_op_validation(lib):
+    ok = 0x10000
+    with pytest.raises(taw.TawError) as e:
+        taw.taw_op_gemm(taw.TAW_BF16, 5, 8, 8, 8, ok, 8, ok, 8, ok, 8, taw.TAW_BF16)
+    assert e.value.status == taw.TAW_ERR_SHAPE
+    with pytest.raises(taw.TawError) as e:
+        taw.taw_op_gemm(taw.TAW_BF16, taw.TAW_GEMM_NT, 8, 8, 8, ok, 4, ok, 8, ok, 8, taw.TAW_BF16)
+    assert e.value.status == taw.TAW_ERR_SHAPE           # lda < K
+    with pytest.raises(taw.TawError) as e:
+        taw.taw_op_gemm(taw.TAW_F32, taw.TAW_GEMM_NT, 8, 8, 8, ok, 8, ok, 8, ok, 8, taw.TAW_F32, impl=taw.TAW_IMPL_MFMA)
+    assert e.value.status == taw.TAW_ERR_UNSUPPORTED
+    with pytest.raises(taw.TawError) as e:
+        taw.taw_op_attn_fwd(taw.TAW_F32, 1, 16, 2, 16, ok, ok, ok, impl=taw.TAW_IMPL_MFMA)
+    assert e.value.status == taw.TAW_ERR_UNSUPPORTED
+    with pytest.raises(taw.TawError) as e:
+        taw.taw_op_rope(taw.TAW_F32, 1, 16, 24, 16, ok, 24, ok)
+    assert e.value.status == taw.TAW_ERR_SHAPE           # ncols not a multiple of head_dim
+
+
+def test_missing_library_fails_loudly(monkeypatch, tmp_path):
+    monkeypatch.setattr(taw, "_lib", None)
+    monkeypatch.setattr(taw, "LIB_PATH", str(tmp_path / "nope.so"))
+    with pytest.raises(ImportError):
+        taw.load()
