@@ -73,6 +73,9 @@ def load():
         if not os.path.exists(LIB_PATH):
             raise ImportError(f"{LIB_PATH} not found: build it with `python -m paper_2511_09741_amd.build`; "
                               "there is no fallback path")
+        # torch first: it brings its own HIP runtime (soname libamdhip64.so.7) and the loader then
+        # binds libtaw.so to that one; two HIP runtimes in one process do not both see the GPU.
+        import torch  # noqa: F401
         lib = C.CDLL(LIB_PATH)
         for name, (res, args) in _SIGS.items():
             fn = getattr(lib, name)

@@ -189,8 +189,10 @@ def _attn_case(taw, dtype, B, S, nh, d, impl, seed=0, scale=1.0):
     scratch = torch.empty(B * nh * S, dtype=torch.float32, device="cuda")
     taw.taw_op_attn_bwd(dtype, B, S, nh, d, qkvd, U.to_dev(o_st, dtype), U.to_dev(dO, dtype), lse_ref32, dqkv, scratch, impl)
     got = U.from_dev(dqkv)
-    e_dq = U.tensor_scale_err(got[:, :H], dref[:, :H])
-    e_dk = U.tensor_scale_err(got[:, H:2 * H], dref[:, H:2 * H])
+    # at S = 1 the exact dq and dk are identically zero: measure them on the scale of dv
+    fl = 1e-3 * float(np.max(np.abs(dref[:, 2 * H:])))
+    e_dq = U.tensor_scale_err(got[:, :H], dref[:, :H], floor=fl)
+    e_dk = U.tensor_scale_err(got[:, H:2 * H], dref[:, H:2 * H], floor=fl)
     e_dv = U.tensor_scale_err(got[:, 2 * H:], dref[:, 2 * H:])
     print(f"attn dtype={dtype} B={B} S={S} nh={nh} d={d} impl={impl}: o={e_o:.2e} lse={e_l:.2e} dq={e_dq:.2e} dk={e_dk:.2e} dv={e_dv:.2e}", flush=True)
     assert e_o < tol and e_l < (2e-2 if dtype == I.BF16 else 1e-4)
@@ -242,3 +244,35 @@ def test_weight_stage_double_buffer(taw):
     assert sums.cpu().tolist() == [1.0, 2.0, 3.0, 4.0]
     taw.taw_weight_stage(None, None, 0, copy_stream, None, ready[0])   # bytes == 0 only handles the events
     torch.cuda.synchronize()
+
+
+# ----------------------------------------------------------------------------- MFMA kernels (bf16)
+MFMA_GEMM_SHAPES = {
+    0: [(256, 256, 64), (8, 8, 8), (300, 520, 136), (257, 263, 72), (1000, 264, 4104), (512, 768, 1024), (1, 3, 8)],
+    1: [(256, 256, 64), (8, 8, 8), (300, 520, 136), (257, 264, 72), (1000, 264, 4104), (512, 768, 1024), (1, 8, 8)],
+    2: [(256, 256, 64), (8, 8, 8), (304, 520, 133), (264, 256, 77), (1000, 264, 4100), (512, 768, 1024), (8, 8, 1)],
+}
+
+
+@pytest.mark.parametrize("mode", [0, 1, 2])
+def test_gemm_mfma_shapes(taw, mode):
+    """Several tiles, ragged tails in M, N and K, and degenerate sizes; bf16 output."""
+    for (M, N, K) in MFMA_GEMM_SHAPES[mode]:
+        err = _gemm_case(taw, I.BF16, mode, M, N, K, taw.TAW_IMPL_MFMA, seed=M + N + K)
+        print(f"mfma gemm mode={mode} {M}x{N}x{K}: err={err:.2e}", flush=True)
+
+
+@pytest.mark.parametrize("mode", [0, 1, 2])
+def test_gemm_mfma_epilogues(taw, mode):
+    shp = (520, 264, 200) if mode != 2 else (520, 264, 203)
+    _gemm_case(taw, I.BF16, mode, *shp, taw.TAW_IMPL_MFMA, residual=True)
+    _gemm_case(taw, I.BF16, mode, *shp, taw.TAW_IMPL_MFMA, c_f32=True)
+    _gemm_case(taw, I.BF16, mode, *shp, taw.TAW_IMPL_MFMA, c_f32=True, accumulate=True)
+    _gemm_case(taw, I.BF16, mode, *shp, taw.TAW_IMPL_MFMA, c_f32=True, accumulate=True, residual=True)
+
+
+def test_gemm_mfma_fp32_output_is_accurate(taw):
+    """With fp32 output the only error left is the accumulation order: far below bf16 rounding."""
+    for mode in (0, 1, 2):
+        err = _gemm_case(taw, I.BF16, mode, 264, 512, 2048, taw.TAW_IMPL_MFMA, c_f32=True, seed=mode)
+        assert err < 2e-6, (mode, err)

@@ -9,8 +9,9 @@ from paper_2511_09741_amd import inputs as I
 TOL = {I.F32: 1e-4, I.BF16: 2e-2}   # tensor-scale max error bar per storage dtype
 
 
-def tensor_scale_err(got, ref) -> float:
-    """max_i |got_i - ref_i| / max_i |ref_i|  (element-wise relative error is ill-posed at ref ~ 0)."""
+def tensor_scale_err(got, ref, floor: float = 0.0) -> float:
+    """max_i |got_i - ref_i| / max(max_i |ref_i|, floor)  (element-wise relative error is ill-posed
+    at ref ~ 0; `floor` is for tensors whose exact value is identically zero)."""
     got = np.asarray(got, dtype=np.float64)
     ref = np.asarray(ref, dtype=np.float64)
     assert got.shape == ref.shape, (got.shape, ref.shape)
@@ -18,7 +19,7 @@ def tensor_scale_err(got, ref) -> float:
         return 0.0
     if not np.all(np.isfinite(got)):
         return float("inf")
-    denom = float(np.max(np.abs(ref)))
+    denom = max(float(np.max(np.abs(ref))), floor)
     num = float(np.max(np.abs(got - ref)))
     return num / denom if denom > 0 else num
 
