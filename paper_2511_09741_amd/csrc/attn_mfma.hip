@@ -1,7 +1,603 @@
-// placeholder until the MFMA attention lands
+// Causal softmax attention for head_dim 128 on the gfx950 matrix cores: tiled, online softmax, no
+// S x S matrix in memory.  bf16 operands, fp32 accumulation, fp32 softmax statistics.
+//
+// Layout of the operands: qkv [B*S, 3H] row-major, q | k | v, head h at columns h*128 of each part.
+//
+// All three kernels use v_mfma_f32_32x32x16_bf16.  Its accumulator layout gives lane l column
+// (l & 31) and rows 8(r/4) + 4(l>>5) + r%4 for register r; its operand layout gives lane l row or
+// column (l & 31) and k = 8(l>>5) + 0..7.  The kernels are arranged so that the accumulator of the
+// first product can be fed, converted to bf16 and nothing else, into the operand of the second:
+//
+//   forward / dQ kernel:  S^T[kv][q] = K Q^T  -> lane owns one query column: the softmax row
+//     statistics (max, sum, lse, D) are per-lane scalars; P^T (or dS^T) is then the B operand of
+//     O^T[d][q] += V^T[d][kv] P^T[kv][q]   (dQ^T += K^T dS^T).
+//   dK/dV kernel:  S[q][kv] = Q K^T  -> lane owns one key column; P (dS) is the B operand of
+//     dV^T[d][kv] += dO^T[d][q] P[q][kv]   (dK^T += Q^T dS).
+//
+// The A operands V^T, K^T, dO^T, Q^T are "transposed" tiles: they are read from the row-major LDS
+// tile with ds_read_b64_tr_b16, which returns 4 consecutive rows of one column per lane: exactly
+// the 4-row groups of the accumulator layout.  Nothing is transposed through memory.
+#include "dev_common.h"
 #include "taw_internal.h"
+
 namespace taw {
-bool attn_mfma_supported(int, int, int) { return false; }
-int launch_attn_fwd_mfma(int, int, int, const void*, void*, float*, hipStream_t) { return (int)hipErrorNotSupported; }
-int launch_attn_bwd_mfma(int, int, int, const void*, const void*, const float*, const float*, void*, hipStream_t) { return (int)hipErrorNotSupported; }
+
+namespace {
+
+constexpr int D = 128;             // head_dim
+constexpr int kThreads = 256;      // 4 wavefronts
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+__device__ __forceinline__ s16x4_t lds_read_tr(const bf16_t* p) {
+  return __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4_t __attribute__((address_space(3)))*)(p));
 }
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+__device__ __forceinline__ f32x16_t mfma(bf16x8_t a, bf16x8_t b, f32x16_t c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+
+// ---- row-major [rows][128] bf16 tile in LDS, 16-byte chunks XOR-swizzled ------------------------
+// A row is 256 bytes = one pass over all 64 banks, so the chunk index is the bank group.  One
+// swizzle serves both access patterns:  chunk ^= ((row & 3) << 2) | ((row >> 2) & 3).
+//   natural reads (8 consecutive d of one row per lane, ds_read_b128): 16 consecutive lanes read 16
+//     consecutive rows of one chunk -> 16 distinct bank groups;
+//   transposing reads (4 consecutive rows of one d per lane, ds_read_b64_tr_b16): 32 lanes read
+//     4 rows x 4 chunks -> 16 distinct bank groups.
+__device__ __forceinline__ int swz(int row, int chunk) { return chunk ^ (((row & 3) << 2) | ((row >> 2) & 3)); }
+
+// global -> registers -> LDS for a [ROWS][128] tile: ROWS*16/256 chunks of 16 bytes per thread.
+// src points at (row 0, column 0 of this head); rows at or beyond `limit` are clamped to limit-1.
+template <int N>
+__device__ __forceinline__ void tile_load(u32x4_t (&regs)[N], const bf16_t* src, int64_t ld, int row0, int limit, int tid) {
+  const int c = tid & 15, r0 = tid >> 4;
+#pragma unroll
+  for (int i = 0; i < N; ++i) {
+    int r = row0 + r0 + 16 * i;
+    if (r >= limit) r = limit - 1;
+    regs[i] = *reinterpret_cast<const u32x4_t*>(src + (int64_t)r * ld + c * 8);
+  }
+}
+template <int N>
+__device__ __forceinline__ void tile_store(bf16_t* tile, const u32x4_t (&regs)[N], int tid) {
+  const int c = tid & 15, r0 = tid >> 4;
+#pragma unroll
+  for (int i = 0; i < N; ++i) {
+    const int r = r0 + 16 * i;
+    *reinterpret_cast<u32x4_t*>(tile + r * D + (swz(r, c) << 3)) = regs[i];
+  }
+}
+
+// natural operand: rows row0 + (lane&31), d = 16 ks + 8 (lane>>5) + 0..7
+__device__ __forceinline__ bf16x8_t frag_nat(const bf16_t* tile, int row0, int ks, int lane) {
+  const int r = row0 + (lane & 31), c = 2 * ks + (lane >> 5);
+  return *reinterpret_cast<const bf16x8_t*>(tile + r * D + (swz(r, c) << 3));
+}
+
+// transposed operand for the second product: lane gets column d = d0 + (lane&31) and the 8 rows
+//   row0 + 16 t + {4h..4h+3, 8+4h..8+4h+3},  h = lane>>5,
+// which are the rows that accumulator registers 8t..8t+7 of the first product hold.
+__device__ __forceinline__ bf16x8_t frag_tr(const bf16_t* tile, int row0, int t, int d0, int lane) {
+  const int blk = lane >> 4, i = lane & 15, h = blk >> 1;
+  const int d = d0 + 16 * (blk & 1) + 4 * (i & 3);
+  union { s16x4_t h2[2]; bf16x8_t v; } u;
+#pragma unroll
+  for (int rr = 0; rr < 2; ++rr) {
+    const int r = row0 + 16 * t + 8 * rr + 4 * h + (i >> 2);
+    u.h2[rr] = lds_read_tr(tile + r * D + (swz(r, d >> 3) << 3) + (d & 7));
+  }
+  return u.v;
+}
+
+__device__ __forceinline__ bf16x8_t pack8(const f32x16_t& x, int t) {
+  bf16x8_t p;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) p[j] = (bf16_t)x[8 * t + j];
+  return p;
+}
+
+// =============================================================================== forward
+// Workgroup: one (batch, head, 128*QSUB query rows); wavefront w owns rows 32*QSUB*w .. +32*QSUB.
+// Keys/values stream through LDS in tiles of 64, double buffered.
+template <int QSUB>
+__global__ void __launch_bounds__(kThreads, 1)
+attn_fwd_kernel(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ o, float* __restrict__ lse, int B, int S, int nh, float scale) {
+  constexpr int BQ = 128 * QSUB, WQ = 32 * QSUB, BKV = 64;
+  constexpr int kTile = BKV * D;   // elements
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
+  bf16_t* lds = reinterpret_cast<bf16_t*>(lds_raw);   // [stage][K tile | V tile]
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, hh = lane >> 5;
+  const int nqt = (S + BQ - 1) / BQ;
+  const int bh = blockIdx.x % (B * nh);
+  const int qt = nqt - 1 - blockIdx.x / (B * nh);      // longest rows first
+  const int b = bh / nh, h = bh % nh;
+  const int64_t H = (int64_t)nh * D, ld = 3 * H;
+  const bf16_t* qbase = qkv + (int64_t)b * S * ld + (int64_t)h * D;
+  const bf16_t* kbase = qbase + H;
+  const bf16_t* vbase = qbase + 2 * H;
+  const int q0 = qt * BQ, q0w = q0 + wave * WQ;
+  const float c = scale * kLog2e;
+
+  // Q as B operands, straight from global memory
+  bf16x8_t qf[QSUB][8];
+#pragma unroll
+  for (int qs = 0; qs < QSUB; ++qs) {
+    int row = q0w + qs * 32 + (lane & 31);
+    if (row >= S) row = S - 1;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks)
+      qf[qs][ks] = *reinterpret_cast<const bf16x8_t*>(qbase + (int64_t)row * ld + 16 * ks + 8 * hh);
+  }
+
+  f32x16_t oacc[QSUB][4];
+  float m[QSUB], l[QSUB];
+#pragma unroll
+  for (int qs = 0; qs < QSUB; ++qs) {
+    m[qs] = -INFINITY; l[qs] = 0.f;
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) oacc[qs][dt][r] = 0.f;
+  }
+
+  const int kv_end = (q0 + BQ < S) ? q0 + BQ : S;
+  const int nkv = (kv_end + BKV - 1) / BKV;
+  u32x4_t rk[4], rv[4];
+  tile_load(rk, kbase, ld, 0, S, tid);
+  tile_load(rv, vbase, ld, 0, S, tid);
+  tile_store(lds, rk, tid);
+  tile_store(lds + kTile, rv, tid);
+  __syncthreads();
+
+  for (int j = 0; j < nkv; ++j) {
+    const bf16_t* sk = lds + (j & 1) * 2 * kTile;
+    const bf16_t* sv = sk + kTile;
+    const bool more = j + 1 < nkv;
+    if (more) {
+      tile_load(rk, kbase, ld, (j + 1) * BKV, S, tid);
+      tile_load(rv, vbase, ld, (j + 1) * BKV, S, tid);
+    }
+    const int kv0 = j * BKV;
+    if (kv0 <= q0w + WQ - 1) {                        // some key of the tile is visible to this wavefront
+      f32x16_t s[QSUB][2];
+#pragma unroll
+      for (int qs = 0; qs < QSUB; ++qs)
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) s[qs][kb][r] = 0.f;
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) {
+          const bf16x8_t kf = frag_nat(sk, kb * 32, ks, lane);
+#pragma unroll
+          for (int qs = 0; qs < QSUB; ++qs) s[qs][kb] = mfma(kf, qf[qs][ks], s[qs][kb]);
+        }
+      const bool need_mask = kv0 + BKV - 1 > q0w;
+      bf16x8_t pf[QSUB][2][2];
+#pragma unroll
+      for (int qs = 0; qs < QSUB; ++qs) {
+        const int qidx = q0w + qs * 32 + (lane & 31);
+        float mx = -INFINITY;
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            float t = s[qs][kb][r] * c;
+            if (need_mask) {
+              const int kv = kv0 + kb * 32 + 8 * (r >> 2) + 4 * hh + (r & 3);
+              t = kv > qidx ? -INFINITY : t;
+            }
+            s[qs][kb][r] = t;
+            mx = fmaxf(mx, t);
+          }
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        const float m_new = fmaxf(m[qs], mx);
+        const float alpha = fast_exp2(m[qs] - m_new);
+        m[qs] = m_new;
+        float rs = 0.f;
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const float p = fast_exp2(s[qs][kb][r] - m_new);
+            s[qs][kb][r] = p;
+            rs += p;
+          }
+        l[qs] = l[qs] * alpha + rs;
+#pragma unroll
+        for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) oacc[qs][dt][r] *= alpha;
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+          for (int t = 0; t < 2; ++t) pf[qs][kb][t] = pack8(s[qs][kb], t);
+      }
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+          for (int dt = 0; dt < 4; ++dt) {
+            const bf16x8_t vf = frag_tr(sv, kb * 32, t, dt * 32, lane);
+#pragma unroll
+            for (int qs = 0; qs < QSUB; ++qs) oacc[qs][dt] = mfma(vf, pf[qs][kb][t], oacc[qs][dt]);
+          }
+    }
+    if (more) {
+      bf16_t* dk = lds + ((j + 1) & 1) * 2 * kTile;
+      tile_store(dk, rk, tid);
+      tile_store(dk + kTile, rv, tid);
+    }
+    __syncthreads();
+  }
+
+  // ---- epilogue: O^T accumulators -> [q][136] bf16 staging in LDS -> coalesced rows of o
+  constexpr int OLD = 136;
+  bf16_t* ob = lds + wave * (WQ * OLD);
+#pragma unroll
+  for (int qs = 0; qs < QSUB; ++qs) {
+    const float lsum = l[qs] + __shfl_xor(l[qs], 32, 64);
+    const float inv = 1.0f / lsum;
+    const int qrow = qs * 32 + (lane & 31);
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+      for (int r4 = 0; r4 < 4; ++r4) {
+        bf16x4_t pk;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) pk[e] = (bf16_t)(oacc[qs][dt][4 * r4 + e] * inv);
+        *reinterpret_cast<bf16x4_t*>(ob + qrow * OLD + dt * 32 + 8 * r4 + 4 * hh) = pk;
+      }
+    const int qidx = q0w + qrow;
+    if (hh == 0 && qidx < S) lse[((int64_t)b * nh + h) * S + qidx] = m[qs] * kLn2 + logf(lsum);
+  }
+  __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0): this wavefront's LDS writes are done
+  __builtin_amdgcn_wave_barrier();
+  bf16_t* obase = o + (int64_t)b * S * H + (int64_t)h * D;
+#pragma unroll
+  for (int it = 0; it < WQ * 16 / 64; ++it) {
+    const int idx = it * 64 + lane, row = idx >> 4, ch = idx & 15;
+    if (q0w + row < S)
+      *reinterpret_cast<u32x4_t*>(obase + (int64_t)(q0w + row) * H + ch * 8) = *reinterpret_cast<const u32x4_t*>(ob + row * OLD + ch * 8);
+  }
+}
+
+// ---- shared epilogue: a wavefront's transposed accumulators X^T[128 d][32 rows] (lane = row,
+// registers = d) -> [32][136] bf16 staging in LDS -> coalesced 16-byte stores of rows of `out`
+// (row stride ld_out elements).  Rows at or beyond `limit` are dropped.
+__device__ __forceinline__ void store_rows_T(const f32x16_t (&acc)[4], float mul, bf16_t* stage, bf16_t* out,
+                                             int64_t ld_out, int row0, int limit, int lane) {
+  constexpr int OLD = 136;
+  const int hh = lane >> 5, lrow = lane & 31;
+#pragma unroll
+  for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+    for (int r4 = 0; r4 < 4; ++r4) {
+      bf16x4_t pk;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) pk[e] = (bf16_t)(acc[dt][4 * r4 + e] * mul);
+      *reinterpret_cast<bf16x4_t*>(stage + lrow * OLD + dt * 32 + 8 * r4 + 4 * hh) = pk;
+    }
+  __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0)
+  __builtin_amdgcn_wave_barrier();
+#pragma unroll
+  for (int it = 0; it < 8; ++it) {
+    const int idx = it * 64 + lane, row = idx >> 4, ch = idx & 15;
+    if (row0 + row < limit)
+      *reinterpret_cast<u32x4_t*>(out + (int64_t)(row0 + row) * ld_out + ch * 8) = *reinterpret_cast<const u32x4_t*>(stage + row * OLD + ch * 8);
+  }
+  __builtin_amdgcn_s_waitcnt(0xc07f);
+  __builtin_amdgcn_wave_barrier();
+}
+
+// =============================================================================== backward: dK, dV
+// Workgroup: one (batch, head, 128 keys); wavefront w owns keys 32w..32w+31 and keeps their K and V
+// rows in registers as B operands.  Query rows stream through LDS in blocks of 64 (Q and dO tiles,
+// plus lse and D), from the diagonal to the end of the sequence.
+//   S = Q K^T;  P = exp(S/sqrt(d) - lse);  dP = dO V^T;  dS = P (dP - D)
+//   dV^T += dO^T P;   dK^T += Q^T dS  (scaled by 1/sqrt(d) at the end)
+__global__ void __launch_bounds__(kThreads, 1)
+attn_bwd_dkv_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dO, const float* __restrict__ lse,
+                    const float* __restrict__ Dsum, bf16_t* __restrict__ dqkv, int B, int S, int nh, float scale) {
+  constexpr int BKVW = 128, BQ = 64;
+  constexpr int kTile = BQ * D;
+  constexpr int kStage = 2 * kTile + 2 * 2 * BQ;   // Q tile, dO tile (bf16) + lse2[64], D[64] (fp32 = 2 bf16 slots each)
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
+  bf16_t* lds = reinterpret_cast<bf16_t*>(lds_raw);
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, hh = lane >> 5;
+  const int nkt = (S + BKVW - 1) / BKVW;
+  const int bh = blockIdx.x % (B * nh);
+  const int kt = blockIdx.x / (B * nh);                 // early key tiles see the most queries: they go first
+  const int b = bh / nh, h = bh % nh;
+  const int64_t H = (int64_t)nh * D, ld = 3 * H;
+  const bf16_t* qbase = qkv + (int64_t)b * S * ld + (int64_t)h * D;
+  const bf16_t* kbase = qbase + H;
+  const bf16_t* vbase = qbase + 2 * H;
+  const bf16_t* dobase = dO + (int64_t)b * S * H + (int64_t)h * D;
+  const float* lbase = lse + ((int64_t)b * nh + h) * S;
+  const float* dbase = Dsum + ((int64_t)b * nh + h) * S;
+  const int kv0 = kt * BKVW, kv0w = kv0 + wave * 32;
+  const float c = scale * kLog2e;
+  (void)nkt;
+
+  bf16x8_t kf[8], vf[8];
+  {
+    int row = kv0w + (lane & 31);
+    if (row >= S) row = S - 1;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) {
+      kf[ks] = *reinterpret_cast<const bf16x8_t*>(kbase + (int64_t)row * ld + 16 * ks + 8 * hh);
+      vf[ks] = *reinterpret_cast<const bf16x8_t*>(vbase + (int64_t)row * ld + 16 * ks + 8 * hh);
+    }
+  }
+  f32x16_t dk[4], dv[4];
+#pragma unroll
+  for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) { dk[dt][r] = 0.f; dv[dt][r] = 0.f; }
+
+  const int jb = kv0 / BQ, je = (S + BQ - 1) / BQ;      // query blocks jb .. je-1
+  u32x4_t rq[4], rdo[4];
+  float rl = 0.f, rd = 0.f;                              // threads 0..63 stage lse2 / D of the block
+  auto stage_load = [&](int j) {
+    tile_load(rq, qbase, ld, j * BQ, S, tid);
+    tile_load(rdo, dobase, H, j * BQ, S, tid);
+    if (tid < BQ) {
+      int row = j * BQ + tid;
+      if (row >= S) row = S - 1;
+      rl = lbase[row] * kLog2e;
+      rd = dbase[row];
+    }
+  };
+  auto stage_store = [&](int st) {
+    bf16_t* base = lds + st * kStage;
+    tile_store(base, rq, tid);
+    tile_store(base + kTile, rdo, tid);
+    float* f = reinterpret_cast<float*>(base + 2 * kTile);
+    if (tid < BQ) { f[tid] = rl; f[BQ + tid] = rd; }
+  };
+  if (jb < je) {
+    stage_load(jb);
+    stage_store(0);
+  }
+  __syncthreads();
+
+  for (int j = jb; j < je; ++j) {
+    const bf16_t* sq = lds + ((j - jb) & 1) * kStage;
+    const bf16_t* sdo = sq + kTile;
+    const float* sl = reinterpret_cast<const float*>(sq + 2 * kTile);
+    const float* sd = sl + BQ;
+    const bool more = j + 1 < je;
+    if (more) stage_load(j + 1);
+    const int qb0 = j * BQ;
+    if (qb0 + BQ - 1 >= kv0w) {                          // some query of the block sees this wavefront's keys
+#pragma unroll
+      for (int qb = 0; qb < 2; ++qb) {
+        const int qrow0 = qb0 + qb * 32;
+        if (qrow0 + 31 < kv0w) continue;                 // wavefront-uniform
+        f32x16_t sacc, pacc;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) { sacc[r] = 0.f; pacc[r] = 0.f; }
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) {
+          sacc = mfma(frag_nat(sq, qb * 32, ks, lane), kf[ks], sacc);
+          pacc = mfma(frag_nat(sdo, qb * 32, ks, lane), vf[ks], pacc);
+        }
+        const bool need_mask = (qrow0 < kv0w + 31) || (qrow0 + 31 >= S);
+        const int kvi = kv0w + (lane & 31);
+#pragma unroll
+        for (int r4 = 0; r4 < 4; ++r4) {
+          const int rbase = qb * 32 + 8 * r4 + 4 * hh;
+          const f32x4_t l4 = *reinterpret_cast<const f32x4_t*>(sl + rbase);
+          const f32x4_t d4 = *reinterpret_cast<const f32x4_t*>(sd + rbase);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const int r = 4 * r4 + e;
+            float p = fast_exp2(sacc[r] * c - l4[e]);
+            if (need_mask) {
+              const int qi = qb0 + rbase + e;
+              p = (kvi > qi || qi >= S) ? 0.f : p;
+            }
+            sacc[r] = p;
+            pacc[r] = p * (pacc[r] - d4[e]);
+          }
+        }
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+          const bf16x8_t pb = pack8(sacc, t), dsb = pack8(pacc, t);
+#pragma unroll
+          for (int dt = 0; dt < 4; ++dt) {
+            dv[dt] = mfma(frag_tr(sdo, qb * 32, t, dt * 32, lane), pb, dv[dt]);
+            dk[dt] = mfma(frag_tr(sq, qb * 32, t, dt * 32, lane), dsb, dk[dt]);
+          }
+        }
+      }
+    }
+    if (more) stage_store((j + 1 - jb) & 1);
+    __syncthreads();
+  }
+
+  bf16_t* stage = lds + wave * (32 * 136);
+  bf16_t* dkout = dqkv + (int64_t)b * S * ld + H + (int64_t)h * D;
+  bf16_t* dvout = dkout + H;
+  store_rows_T(dk, scale, stage, dkout, ld, kv0w, S, lane);
+  store_rows_T(dv, 1.0f, stage, dvout, ld, kv0w, S, lane);
+}
+
+// =============================================================================== backward: dQ
+// Workgroup: one (batch, head, 128*QSUB query rows); wavefront w owns 32*QSUB of them and keeps their
+// Q and dO rows in registers as B operands.  Keys/values stream through LDS in tiles of 64 up to the
+// diagonal.   S^T = K Q^T;  P^T = exp(S^T/sqrt(d) - lse);  dP^T = V dO^T;  dS^T = P^T (dP^T - D);
+//   dQ^T += K^T dS^T  (scaled by 1/sqrt(d) at the end)
+template <int QSUB>
+__global__ void __launch_bounds__(kThreads, 1)
+attn_bwd_dq_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dO, const float* __restrict__ lse,
+                   const float* __restrict__ Dsum, bf16_t* __restrict__ dqkv, int B, int S, int nh, float scale) {
+  constexpr int BQ = 128 * QSUB, WQ = 32 * QSUB, BKV = 64;
+  constexpr int kTile = BKV * D;
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
+  bf16_t* lds = reinterpret_cast<bf16_t*>(lds_raw);   // [stage][K tile | V tile]
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, hh = lane >> 5;
+  const int nqt = (S + BQ - 1) / BQ;
+  const int bh = blockIdx.x % (B * nh);
+  const int qt = nqt - 1 - blockIdx.x / (B * nh);
+  const int b = bh / nh, h = bh % nh;
+  const int64_t H = (int64_t)nh * D, ld = 3 * H;
+  const bf16_t* qbase = qkv + (int64_t)b * S * ld + (int64_t)h * D;
+  const bf16_t* kbase = qbase + H;
+  const bf16_t* vbase = qbase + 2 * H;
+  const bf16_t* dobase = dO + (int64_t)b * S * H + (int64_t)h * D;
+  const int q0 = qt * BQ, q0w = q0 + wave * WQ;
+  const float c = scale * kLog2e;
+
+  bf16x8_t qf[QSUB][8], dof[QSUB][8];
+  float l2[QSUB], dsum[QSUB];
+  f32x16_t dq[QSUB][4];
+#pragma unroll
+  for (int qs = 0; qs < QSUB; ++qs) {
+    int row = q0w + qs * 32 + (lane & 31);
+    if (row >= S) row = S - 1;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) {
+      qf[qs][ks] = *reinterpret_cast<const bf16x8_t*>(qbase + (int64_t)row * ld + 16 * ks + 8 * hh);
+      dof[qs][ks] = *reinterpret_cast<const bf16x8_t*>(dobase + (int64_t)row * H + 16 * ks + 8 * hh);
+    }
+    l2[qs] = lse[((int64_t)b * nh + h) * S + row] * kLog2e;
+    dsum[qs] = Dsum[((int64_t)b * nh + h) * S + row];
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) dq[qs][dt][r] = 0.f;
+  }
+
+  const int kv_end = (q0 + BQ < S) ? q0 + BQ : S;
+  const int nkv = (kv_end + BKV - 1) / BKV;
+  u32x4_t rk[4], rv[4];
+  tile_load(rk, kbase, ld, 0, S, tid);
+  tile_load(rv, vbase, ld, 0, S, tid);
+  tile_store(lds, rk, tid);
+  tile_store(lds + kTile, rv, tid);
+  __syncthreads();
+
+  for (int j = 0; j < nkv; ++j) {
+    const bf16_t* sk = lds + (j & 1) * 2 * kTile;
+    const bf16_t* sv = sk + kTile;
+    const bool more = j + 1 < nkv;
+    if (more) {
+      tile_load(rk, kbase, ld, (j + 1) * BKV, S, tid);
+      tile_load(rv, vbase, ld, (j + 1) * BKV, S, tid);
+    }
+    const int kv0 = j * BKV;
+    if (kv0 <= q0w + WQ - 1) {
+      const bool need_mask = kv0 + BKV - 1 > q0w;
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb) {
+        f32x16_t sacc[QSUB], pacc[QSUB];
+#pragma unroll
+        for (int qs = 0; qs < QSUB; ++qs)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) { sacc[qs][r] = 0.f; pacc[qs][r] = 0.f; }
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) {
+          const bf16x8_t ka = frag_nat(sk, kb * 32, ks, lane);
+          const bf16x8_t va = frag_nat(sv, kb * 32, ks, lane);
+#pragma unroll
+          for (int qs = 0; qs < QSUB; ++qs) {
+            sacc[qs] = mfma(ka, qf[qs][ks], sacc[qs]);
+            pacc[qs] = mfma(va, dof[qs][ks], pacc[qs]);
+          }
+        }
+        bf16x8_t dsb[QSUB][2];
+#pragma unroll
+        for (int qs = 0; qs < QSUB; ++qs) {
+          const int qidx = q0w + qs * 32 + (lane & 31);
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            float p = fast_exp2(sacc[qs][r] * c - l2[qs]);
+            if (need_mask) {
+              const int kv = kv0 + kb * 32 + 8 * (r >> 2) + 4 * hh + (r & 3);
+              p = kv > qidx ? 0.f : p;
+            }
+            pacc[qs][r] = p * (pacc[qs][r] - dsum[qs]);
+          }
+#pragma unroll
+          for (int t = 0; t < 2; ++t) dsb[qs][t] = pack8(pacc[qs], t);
+        }
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+          for (int dt = 0; dt < 4; ++dt) {
+            const bf16x8_t kt_ = frag_tr(sk, kb * 32, t, dt * 32, lane);
+#pragma unroll
+            for (int qs = 0; qs < QSUB; ++qs) dq[qs][dt] = mfma(kt_, dsb[qs][t], dq[qs][dt]);
+          }
+      }
+    }
+    if (more) {
+      bf16_t* dk = lds + ((j + 1) & 1) * 2 * kTile;
+      tile_store(dk, rk, tid);
+      tile_store(dk + kTile, rv, tid);
+    }
+    __syncthreads();
+  }
+
+  bf16_t* stage = lds + wave * (32 * 136);
+  bf16_t* dqout = dqkv + (int64_t)b * S * ld + (int64_t)h * D;
+#pragma unroll
+  for (int qs = 0; qs < QSUB; ++qs) store_rows_T(dq[qs], scale, stage, dqout, ld, q0w + qs * 32, S, lane);
+}
+
+template <int QSUB>
+int launch_fwd_t(int B, int S, int nh, const void* qkv, void* o, float* lse, hipStream_t st) {
+  constexpr int BQ = 128 * QSUB;
+  constexpr size_t lds_main = 2 * 2 * 64 * D * sizeof(bf16_t);
+  constexpr size_t lds_epi = 4 * 32 * QSUB * 136 * sizeof(bf16_t);
+  constexpr size_t lds = lds_main > lds_epi ? lds_main : lds_epi;
+  hipError_t e = hipFuncSetAttribute((const void*)attn_fwd_kernel<QSUB>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  if (e != hipSuccess) return (int)e;
+  const int nqt = (S + BQ - 1) / BQ;
+  const float scale = 1.0f / sqrtf((float)D);
+  hipLaunchKernelGGL((attn_fwd_kernel<QSUB>), dim3((unsigned)(nqt * B * nh)), dim3(kThreads), lds, st, (const bf16_t*)qkv, (bf16_t*)o, lse, B, S, nh, scale);
+  return (int)hipGetLastError();
+}
+
+}  // namespace
+
+bool attn_mfma_supported(int dtype, int S, int d) { return dtype == DT_BF16 && d == D && S >= 1; }
+
+int launch_attn_fwd_mfma(int B, int S, int nh, const void* qkv, void* o, float* lse, hipStream_t st) {
+  return launch_fwd_t<2>(B, S, nh, qkv, o, lse, st);
+}
+
+int launch_attn_bwd_mfma(int B, int S, int nh, const void* qkv, const void* dO, const float* lse, const float* Dv, void* dqkv, hipStream_t st) {
+  const float scale = 1.0f / sqrtf((float)D);
+  {
+    constexpr size_t lds = 2 * (2 * 64 * D * sizeof(bf16_t) + 2 * 64 * sizeof(float));
+    hipError_t e = hipFuncSetAttribute((const void*)attn_bwd_dkv_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return (int)e;
+    const int nkt = (S + 127) / 128;
+    hipLaunchKernelGGL(attn_bwd_dkv_kernel, dim3((unsigned)(nkt * B * nh)), dim3(kThreads), lds, st, (const bf16_t*)qkv, (const bf16_t*)dO, lse, Dv,
+                       (bf16_t*)dqkv, B, S, nh, scale);
+    int rc = (int)hipGetLastError();
+    if (rc) return rc;
+  }
+  {
+    constexpr int QSUB = 1;
+    constexpr size_t lds = 2 * 2 * 64 * D * sizeof(bf16_t);
+    hipError_t e = hipFuncSetAttribute((const void*)attn_bwd_dq_kernel<QSUB>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return (int)e;
+    const int nqt = (S + 128 * QSUB - 1) / (128 * QSUB);
+    hipLaunchKernelGGL((attn_bwd_dq_kernel<QSUB>), dim3((unsigned)(nqt * B * nh)), dim3(kThreads), lds, st, (const bf16_t*)qkv, (const bf16_t*)dO, lse, Dv,
+                       (bf16_t*)dqkv, B, S, nh, scale);
+    return (int)hipGetLastError();
+  }
+}
+
+}  // namespace taw

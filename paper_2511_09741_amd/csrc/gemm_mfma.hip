@@ -71,38 +71,38 @@ struct TileLoader {
     }
   }
   // loads the step starting at k0; chunks whose k lies at or beyond K come back as zeros
-  __device__ __forceinline__ void load(uint4 (&regs)[8], int64_t k0, int64_t K) const {
+  __device__ __forceinline__ void load(u32x4_t (&regs)[8], int64_t k0, int64_t K) const {
     const bf16_t* p = base + (k0 / BK) * kstep;
     if (KC) {
       const bool valid = k0 + kfirst < K;
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
-        uint4 v = *reinterpret_cast<const uint4*>(p + (valid ? off[i] : off[i] - kfirst));
-        regs[i] = valid ? v : make_uint4(0, 0, 0, 0);
+        u32x4_t v = *reinterpret_cast<const u32x4_t*>(p + (valid ? off[i] : off[i] - kfirst));
+        regs[i] = valid ? v : u32x4_t{0u, 0u, 0u, 0u};
       }
     } else {
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
         const bool valid = k0 + kfirst + 8 * i < K;
-        uint4 v = *reinterpret_cast<const uint4*>(valid ? p + off[i] : base);
-        regs[i] = valid ? v : make_uint4(0, 0, 0, 0);
+        u32x4_t v = *reinterpret_cast<const u32x4_t*>(valid ? p + off[i] : base);
+        regs[i] = valid ? v : u32x4_t{0u, 0u, 0u, 0u};
       }
     }
   }
-  __device__ __forceinline__ void store(bf16_t* tile, const uint4 (&regs)[8], int tid) const {
+  __device__ __forceinline__ void store(bf16_t* tile, const u32x4_t (&regs)[8], int tid) const {
     if (KC) {
       const int c = tid & 7, r0 = tid >> 3;
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
         const int r = r0 + 32 * i;
-        *reinterpret_cast<uint4*>(tile + r * BK + ((c ^ ((r >> 1) & 7)) << 3)) = regs[i];
+        *reinterpret_cast<u32x4_t*>(tile + r * BK + ((c ^ ((r >> 1) & 7)) << 3)) = regs[i];
       }
     } else {
       const int c = tid & 31, k0 = tid >> 5;
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
         const int k = k0 + 8 * i;
-        *reinterpret_cast<uint4*>(tile + k * 256 + ((c ^ ((k & 3) << 2)) << 3)) = regs[i];
+        *reinterpret_cast<u32x4_t*>(tile + k * 256 + ((c ^ ((k & 3) << 2)) << 3)) = regs[i];
       }
     }
   }
@@ -168,7 +168,7 @@ gemm_mfma_kernel(int64_t M, int64_t N, int64_t K, const bf16_t* __restrict__ A, 
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  uint4 ra[8], rb[8];
+  u32x4_t ra[8], rb[8];
   la.load(ra, 0, K);
   lb.load(rb, 0, K);
   la.store(lds, ra, tid);

@@ -85,3 +85,11 @@ def test_microbatch_accumulation_matches_oracle_sum(taw):
     got = L.grads()
     for k in Gsum:
         assert U.tensor_scale_err(got[k], Gsum[k]) < 1e-4, k
+
+
+@pytest.mark.parametrize("B,S,nh,I_,sigma", [(1, 256, 2, 384, 0.02), (2, 333, 2, 392, 0.05), (1, 1024, 4, 1408, 0.02), (1, 77, 1, 136, 0.1)])
+def test_bf16_layer_on_mfma_kernels(taw, B, S, nh, I_, sigma):
+    """bf16, head_dim 128: the MFMA GEMM and attention kernels carry the layer.  Sizes span several
+    tiles and leave ragged tails in tokens, widths and the SwiGLU dimension."""
+    cfg = I.LayerConfig("bf16-mfma", I.BF16, B, S, nh * 128, nh, 128, I_, sigma_w=sigma)
+    U.check_layer(taw, cfg, seed=B + S, gamma_jitter=0.1)

@@ -276,3 +276,14 @@ def test_gemm_mfma_fp32_output_is_accurate(taw):
     for mode in (0, 1, 2):
         err = _gemm_case(taw, I.BF16, mode, 264, 512, 2048, taw.TAW_IMPL_MFMA, c_f32=True, seed=mode)
         assert err < 2e-6, (mode, err)
+
+
+@pytest.mark.parametrize("B,S,nh", [(1, 64, 1), (1, 256, 2), (2, 333, 2), (1, 1, 1), (1, 1000, 1), (1, 130, 3)])
+def test_attention_mfma(taw, B, S, nh):
+    """Tiled online-softmax kernels: several query/key tiles, ragged S, S = 1, more than one head and batch."""
+    _attn_case(taw, I.BF16, B, S, nh, 128, taw.TAW_IMPL_MFMA, seed=S + nh)
+
+
+def test_attention_mfma_peaked_scores(taw):
+    """Scores of order 10: the running maximum moves a lot between key tiles."""
+    _attn_case(taw, I.BF16, 1, 700, 2, 128, taw.TAW_IMPL_MFMA, seed=9, scale=3.0)
