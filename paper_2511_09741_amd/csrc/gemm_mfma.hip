@@ -70,39 +70,41 @@ struct TileLoader {
       kfirst = k0;
     }
   }
-  // loads the step starting at k0; chunks whose k lies at or beyond K come back as zeros
+  // issues the loads of the step starting at k0 (addresses of chunks at or beyond K are redirected
+  // to a valid place); nothing here touches the loaded registers, so the loads stay in flight
+  // while the caller multiplies the previous step
   __device__ __forceinline__ void load(u32x4_t (&regs)[8], int64_t k0, int64_t K) const {
     const bf16_t* p = base + (k0 / BK) * kstep;
     if (KC) {
-      const bool valid = k0 + kfirst < K;
+      const int adj = (k0 + kfirst < K) ? 0 : kfirst;
 #pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        u32x4_t v = *reinterpret_cast<const u32x4_t*>(p + (valid ? off[i] : off[i] - kfirst));
-        regs[i] = valid ? v : u32x4_t{0u, 0u, 0u, 0u};
-      }
+      for (int i = 0; i < 8; ++i) regs[i] = *reinterpret_cast<const u32x4_t*>(p + (off[i] - adj));
     } else {
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
         const bool valid = k0 + kfirst + 8 * i < K;
-        u32x4_t v = *reinterpret_cast<const u32x4_t*>(valid ? p + off[i] : base);
-        regs[i] = valid ? v : u32x4_t{0u, 0u, 0u, 0u};
+        regs[i] = *reinterpret_cast<const u32x4_t*>(valid ? p + off[i] : base);
       }
     }
   }
-  __device__ __forceinline__ void store(bf16_t* tile, const u32x4_t (&regs)[8], int tid) const {
+  // registers -> LDS tile of the step that started at k0; chunks at or beyond K are written as zeros
+  __device__ __forceinline__ void store(bf16_t* tile, const u32x4_t (&regs)[8], int tid, int64_t k0, int64_t K) const {
+    const u32x4_t zero = {0u, 0u, 0u, 0u};
     if (KC) {
       const int c = tid & 7, r0 = tid >> 3;
+      const bool valid = k0 + kfirst < K;
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
         const int r = r0 + 32 * i;
-        *reinterpret_cast<u32x4_t*>(tile + r * BK + ((c ^ ((r >> 1) & 7)) << 3)) = regs[i];
+        *reinterpret_cast<u32x4_t*>(tile + r * BK + ((c ^ ((r >> 1) & 7)) << 3)) = valid ? regs[i] : zero;
       }
     } else {
-      const int c = tid & 31, k0 = tid >> 5;
+      const int c = tid & 31, kr = tid >> 5;
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
-        const int k = k0 + 8 * i;
-        *reinterpret_cast<u32x4_t*>(tile + k * 256 + ((c ^ ((k & 3) << 2)) << 3)) = regs[i];
+        const int k = kr + 8 * i;
+        const bool valid = k0 + k < K;
+        *reinterpret_cast<u32x4_t*>(tile + k * 256 + ((c ^ ((k & 3) << 2)) << 3)) = valid ? regs[i] : zero;
       }
     }
   }
@@ -171,8 +173,8 @@ gemm_mfma_kernel(int64_t M, int64_t N, int64_t K, const bf16_t* __restrict__ A, 
   u32x4_t ra[8], rb[8];
   la.load(ra, 0, K);
   lb.load(rb, 0, K);
-  la.store(lds, ra, tid);
-  lb.store(lds + kTileElems, rb, tid);
+  la.store(lds, ra, tid, 0, K);
+  lb.store(lds + kTileElems, rb, tid, 0, K);
   __syncthreads();
 
   const int64_t nk = (K + BK - 1) / BK;
@@ -198,8 +200,8 @@ gemm_mfma_kernel(int64_t M, int64_t N, int64_t K, const bf16_t* __restrict__ A, 
     }
     if (more) {
       bf16_t* da = lds + ((kt + 1) & 1) * kStageElems;
-      la.store(da, ra, tid);
-      lb.store(da + kTileElems, rb, tid);
+      la.store(da, ra, tid, (kt + 1) * BK, K);
+      lb.store(da + kTileElems, rb, tid, (kt + 1) * BK, K);
     }
     __syncthreads();
   }
