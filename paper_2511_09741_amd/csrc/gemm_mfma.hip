@@ -19,6 +19,8 @@
 // Workgroup ids are remapped so that the 8 XCDs (ids are dealt round-robin to them) each work on a
 // contiguous band of tiles and, inside a band, on groups of 8 tile rows: tiles that share an
 // operand panel then share one XCD's L2.
+#include <type_traits>
+
 #include "dev_common.h"
 #include "taw_internal.h"
 
@@ -235,6 +237,341 @@ gemm_mfma_kernel(int64_t M, int64_t N, int64_t K, const bf16_t* __restrict__ A, 
   }
 }
 
+// =============================================================================== pipelined kernel
+// Same tile shape and operand layouts, different data movement: K advances in steps of 32 through
+// a 4-stage ring of LDS tiles (4 x 32 KiB) filled by direct global->LDS loads
+// (global_load_lds_dwordx4: no staging registers, no LDS store instructions).  Each lane picks
+// the global chunk whose swizzled home is the LDS slot its lane number writes, so the swizzle
+// costs nothing.  Per K step a wavefront issues its 8 loads for the tile three steps ahead, waits
+// (vmcnt) until the tile two steps ahead has landed, and meets the other wavefronts at one raw
+// s_barrier.  The first operand fragments of the next tile are read before that barrier (the tile
+// became visible at the previous one), so no LDS latency is exposed after it.
+//
+// The instruction stream of a step is laid out by hand as 16 groups of {2 MFMA, 1 operand
+// fragment read, 1 direct load}, each closed by a scheduling barrier: one wavefront per SIMD
+// issues in order, so the matrix pipe only stays busy if the LDS reads, the loads and their few
+// scalar instructions sit in the shadow of the MFMAs instead of in front of them.
+// Needs K % 32 == 0 (the launcher sends other K to the kernel above).
+namespace v2 {
+
+constexpr int BK2 = 32;
+constexpr int kStages = 4;
+constexpr int kOpBytes = 256 * BK2 * 2;          // one operand tile: 16 KiB
+constexpr int kStageBytes = 2 * kOpBytes;        // 32 KiB
+constexpr size_t kLds2 = (size_t)kStages * kStageBytes;   // 128 KiB
+
+typedef __attribute__((address_space(3))) unsigned char lds_u8_t;
+
+// s_waitcnt vmcnt(n) with the other counters left alone (gfx9 encoding: vmcnt[3:0] | expcnt<<4 | lgkmcnt<<8 | vmcnt[5:4]<<14)
+template <int N> __device__ __forceinline__ void wait_vmcnt() {
+  __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (15 << 8) | ((N >> 4) << 14));
+}
+
+// 16 bytes per lane from global memory (64-bit scalar base + 32-bit per-lane byte offset) straight
+// into LDS at lds_addr + 16 * lane (lds_addr wavefront-uniform).
+// Written as inline assembly on purpose: the compiler's wait-count insertion treats every LDS
+// read whose address it cannot disambiguate (the transposing reads are such) as depending on all
+// outstanding LDS-DMA loads and puts s_waitcnt vmcnt(0) in front of it, which would serialise
+// the ring.  Here the loads are invisible to it and the kernel orders them itself: vmcnt waits
+// plus a workgroup barrier before a stage is read, a barrier after its last read before it is
+// refilled.  m0 is not allocatable: the compiler sets it immediately before each use of its own.
+__device__ __forceinline__ void lds_dma16(uint64_t base, unsigned off, unsigned lds_addr) {
+  asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(off), "s"(base), "s"(lds_addr));
+}
+
+// workgroup barrier that also tells the compiler LDS contents changed (the DMA writes are not
+// visible to it): no LDS access may be moved across
+__device__ __forceinline__ void stage_barrier() {
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+}
+
+// One operand of the tile: where its direct loads come from and where its MFMA fragments sit in LDS.
+//   KC tile [256 rows][32 k] (64-byte rows): load instruction j = 4 i + wave covers rows 16 j .. 16 j + 15;
+//      lane l writes slot (l & 3) of row 16 j + (l >> 2); slot s of row r holds chunk s ^ ((r >> 2) & 3).
+//   NC tile [32 k][256 cols] (512-byte rows): load instruction j covers k rows 2 j, 2 j + 1;
+//      lane l writes position (l & 31) of k row 2 j + (l >> 5); position p of row k holds chunk p ^ ((k & 3) << 2).
+// Rows (KC) / column chunks (NC) outside the matrix are clamped to the last valid one: they feed
+// output rows / columns that the epilogue does not store.
+template <bool KC>
+struct Operand {
+  uint64_t base;          // tile origin at the current K position (bytes); wavefront-uniform
+  uint64_t kstep;         // bytes per K step
+  unsigned goff[4];       // per-lane byte offsets of the 4 loads of a step
+  // LDS byte offsets (inside an operand tile) of this lane's fragment reads.
+  //   KC: rd[ks] for MFMA k-step ks; fragment i is 2048 i bytes further (32 rows)
+  //   NC: rd[i] for fragment i; MFMA k-step ks adds 8192, the second transposing read of a fragment 2048
+  unsigned rd[KC ? 2 : 4];
+
+  __device__ __forceinline__ void init(const bf16_t* mat, int64_t ld, int64_t origin, int64_t extent, int w0, int lane, int wave) {
+    if (KC) {
+      base = (uint64_t)(mat + origin * ld);
+      kstep = BK2 * 2;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        int64_t r = 16 * (4 * i + wave) + (lane >> 2);
+        if (origin + r >= extent) r = extent - 1 - origin;
+        const int c = (lane & 3) ^ ((lane >> 4) & 3);
+        goff[i] = (unsigned)(r * ld * 2 + c * 16);
+      }
+      const int r = w0 + (lane & 31);
+#pragma unroll
+      for (int ks = 0; ks < 2; ++ks) rd[ks] = r * 64 + (((2 * ks + (lane >> 5)) ^ ((r >> 2) & 3)) << 4);
+    } else {
+      base = (uint64_t)(mat + origin);
+      kstep = (uint64_t)ld * (BK2 * 2);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int k = 2 * (4 * i + wave) + (lane >> 5);
+        int64_t col = ((lane & 31) ^ ((k & 3) << 2)) * 8;
+        if (origin + col >= extent) col = extent - 8 - origin;
+        goff[i] = (unsigned)((k * ld + col) * 2);
+      }
+      const int blk = lane >> 4, l16 = lane & 15;
+      const int k = 8 * (blk >> 1) + (l16 >> 2);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int n = w0 + 32 * i + 16 * (blk & 1) + 4 * (l16 & 3);
+        rd[i] = k * 512 + (((n >> 3) ^ ((k & 3) << 2)) << 4) + (n & 7) * 2;
+      }
+    }
+  }
+  // direct load number i (0..3) of the current K step into the operand tile at LDS address lds_op
+  __device__ __forceinline__ void dma(int i, unsigned lds_op, int wave) const { lds_dma16(base, goff[i], lds_op + (4 * i + wave) * 1024); }
+  __device__ __forceinline__ void advance() { base += kstep; }
+  // fragment i (32 rows / columns starting at w0 + 32 i) of MFMA k-step ks from the operand tile at op
+  __device__ __forceinline__ bf16x8_t frag(const lds_u8_t* op, int i, int ks) const {
+    if (KC) {
+      return *reinterpret_cast<const __attribute__((address_space(3))) bf16x8_t*>(op + rd[ks] + 2048 * i);
+    } else {
+      union { s16x4_t h[2]; bf16x8_t v; } u;
+#pragma unroll
+      for (int r = 0; r < 2; ++r)
+        u.h[r] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4_t __attribute__((address_space(3)))*)(op + rd[i] + 8192 * ks + 2048 * r));
+      return u.v;
+    }
+  }
+};
+
+// order in which a half step multiplies its 4 x 4 fragment pairs, two per group, and the fragment
+// each group reads for the following half step (0..3 = A fragment, 4..7 = B fragment): every
+// fragment is read at least five groups before the first MFMA that needs it
+__device__ constexpr int kMfmaI[16] = {0, 0, 1, 1, 0, 1, 2, 2, 2, 0, 1, 2, 3, 3, 3, 3};
+__device__ constexpr int kMfmaJ[16] = {0, 1, 0, 1, 2, 2, 0, 1, 2, 3, 3, 3, 0, 1, 2, 3};
+__device__ constexpr int kReadOrder[8] = {0, 4, 5, 1, 6, 2, 7, 3};
+
+template <int MODE, bool C_F32>
+__global__ void __launch_bounds__(kThreads, 1)
+gemm_dlds_kernel(int64_t M, int64_t N, int64_t K, const bf16_t* __restrict__ A, int64_t lda, const bf16_t* __restrict__ B,
+                 int64_t ldb, void* __restrict__ Cv, int64_t ldc, int accumulate, const void* __restrict__ Rv, int64_t ldr,
+                 int tiles_m, int tiles_n) {
+  constexpr bool A_KC = (MODE != GEMM_TN);
+  constexpr bool B_KC = (MODE == GEMM_NT);
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds2[];
+  const lds_u8_t* lds = (const lds_u8_t*)lds2;
+  const unsigned lds0 = (unsigned)(size_t)lds;
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  // ---- XCD-aware tile id (see file header)
+  const int ntiles = tiles_m * tiles_n;
+  int pid = blockIdx.x;
+  const int n8 = ntiles & ~7;
+  if (pid < n8) pid = (pid & 7) * (n8 >> 3) + (pid >> 3);
+  constexpr int GROUP = 8;
+  const int per_group = GROUP * tiles_n;
+  const int g = pid / per_group;
+  const int gm0 = g * GROUP;
+  const int gsize = (tiles_m - gm0) < GROUP ? (tiles_m - gm0) : GROUP;
+  const int tm = gm0 + (pid % per_group) % gsize;
+  const int tn = (pid % per_group) / gsize;
+  const int64_t m0 = (int64_t)tm * BM, n0 = (int64_t)tn * BN;
+
+  const int wm = (wave >> 1) * 128, wn = (wave & 1) * 128;
+  Operand<A_KC> oa;
+  Operand<B_KC> ob;
+  oa.init(A, lda, m0, M, wm, lane, wave);
+  ob.init(B, ldb, n0, N, wn, lane, wave);
+
+  f32x16_t acc[4][4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  const int nk = (int)(K / BK2);
+  // ---- prologue: tiles 0, 1, 2 in flight; tiles 0 and 1 landed and visible before the loop
+  for (int t = 0; t < 3 && t < nk; ++t) {
+    const unsigned st = lds0 + t * kStageBytes;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) oa.dma(i, st, wave);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) ob.dma(i, st + kOpBytes, wave);
+    oa.advance();
+    ob.advance();
+  }
+  if (nk >= 3) wait_vmcnt<8>(); else wait_vmcnt<0>();
+  stage_barrier();
+  __builtin_amdgcn_sched_barrier(0);
+
+  bf16x8_t fa[2][4], fb[2][4];     // [MFMA k-step of the tile][fragment]
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    fa[0][i] = oa.frag(lds, i, 0);
+    fb[0][i] = ob.frag(lds + kOpBytes, i, 0);
+  }
+
+  // one K step.  First half: MFMAs of k-step 0 (fragments already in registers) with the loads
+  // of tile kt + 3 (its stage held tile kt - 1, which every wavefront finished before the barrier
+  // that ended the previous step) and the fragment reads of k-step 1.  Second half: MFMAs of
+  // k-step 1 with the first fragments of tile kt + 1 (visible since the previous barrier).
+  auto constexpr_mfma = [&](int e, int h) {
+    acc[kMfmaI[e]][kMfmaJ[e]] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[h][kMfmaI[e]], fb[h][kMfmaJ[e]], acc[kMfmaI[e]][kMfmaJ[e]], 0, 0, 0);
+  };
+  auto step = [&](int kt, auto load_c) {
+    constexpr bool LOAD = decltype(load_c)::value;
+    const lds_u8_t* cur = lds + (kt & (kStages - 1)) * kStageBytes;
+    const lds_u8_t* nxt = lds + ((kt + 1) & (kStages - 1)) * kStageBytes;
+    const unsigned dst = lds0 + ((kt + 3) & (kStages - 1)) * kStageBytes;
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const lds_u8_t* src = h == 0 ? cur : nxt;
+#pragma unroll
+      for (int q = 0; q < 8; ++q) {
+        constexpr_mfma(2 * q, h);
+        const int f = kReadOrder[q];
+        if (f < 4) fa[1 - h][f] = oa.frag(src, f, 1 - h);
+        else fb[1 - h][f - 4] = ob.frag(src + kOpBytes, f - 4, 1 - h);
+        __builtin_amdgcn_sched_barrier(0);
+        constexpr_mfma(2 * q + 1, h);
+        if (LOAD && h == 0) {
+          if (q < 4) oa.dma(q, dst, wave);
+          else ob.dma(q - 4, dst + kOpBytes, wave);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+    if (LOAD) {
+      oa.advance();
+      ob.advance();
+      wait_vmcnt<8>();      // tile kt + 2 has landed: only tile kt + 3's 8 loads may still be in flight
+    } else {
+      wait_vmcnt<0>();
+    }
+    stage_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  // the prologue's fragment reads have returned; with nothing outstanding at loop entry the
+  // compiler's lgkmcnt bookkeeping inside the loop only has the loop's own LDS reads to consider
+  __builtin_amdgcn_s_waitcnt(0xc07f);
+  int kt = 0;
+  for (; kt + 3 < nk; ++kt) step(kt, std::true_type{});
+  for (; kt < nk; ++kt) step(kt, std::false_type{});
+
+  // ---- epilogue
+  const int lcol = lane & 31, lrow = 4 * (lane >> 5);
+  if (C_F32) {
+    float* C = static_cast<float*>(Cv);
+    const float* R = static_cast<const float*>(Rv);
+    const bool full = (m0 + BM <= M) && (n0 + BN <= N);
+    for (int i = 0; i < 4; ++i)
+      for (int j = 0; j < 4; ++j) {
+        const int64_t col = n0 + wn + 32 * j + lcol;
+        const int64_t row0 = m0 + wm + 32 * i + lrow;
+        float* cp = C + row0 * ldc + col;
+        const float* rp = R ? R + row0 * ldr + col : nullptr;
+        f32x16_t v;
+        // the selects below keep acc[][] indexed by compile-time constants
+#pragma unroll
+        for (int ii = 0; ii < 4; ++ii)
+#pragma unroll
+          for (int jj = 0; jj < 4; ++jj)
+            if (ii == i && jj == j) v = acc[ii][jj];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int dr = 8 * (r >> 2) + (r & 3);
+          if (full || (row0 + dr < M && col < N)) {
+            float x = v[r];
+            if (rp) x += rp[dr * ldr];
+            if (accumulate) x += cp[dr * ldc];
+            cp[dr * ldc] = x;
+          }
+        }
+      }
+  } else {
+    // fp32 staging in LDS ([32 rows][132] per wavefront), then 16-byte coalesced bf16 rows
+    bf16_t* C = static_cast<bf16_t*>(Cv);
+    const bf16_t* R = static_cast<const bf16_t*>(Rv);
+    constexpr int SLD = 132;
+    float* stg = reinterpret_cast<float*>(lds2) + wave * (32 * SLD);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) stg[(8 * (r >> 2) + lrow + (r & 3)) * SLD + 32 * j + lcol] = acc[i][j][r];
+      __builtin_amdgcn_s_waitcnt(0xc07f);
+      __builtin_amdgcn_wave_barrier();
+      // 32 rows x 128 cols = 512 chunks of 8 columns; lane -> (row = idx >> 4, chunk = idx & 15)
+#pragma unroll
+      for (int it = 0; it < 8; ++it) {
+        const int idx = it * 64 + lane, rr = idx >> 4, ch = idx & 15;
+        const int64_t row = m0 + wm + 32 * i + rr, col = n0 + wn + ch * 8;
+        if (row < M && col < N) {
+          const f32x4_t v0 = *reinterpret_cast<const f32x4_t*>(stg + rr * SLD + ch * 8);
+          const f32x4_t v1 = *reinterpret_cast<const f32x4_t*>(stg + rr * SLD + ch * 8 + 4);
+          float v[8] = {v0[0], v0[1], v0[2], v0[3], v1[0], v1[1], v1[2], v1[3]};
+          if (col + 8 <= N && (ldc & 7) == 0 && (!R || (ldr & 7) == 0)) {
+            if (R) {
+              const bf16x8_t rv = *reinterpret_cast<const bf16x8_t*>(R + row * ldr + col);
+#pragma unroll
+              for (int e = 0; e < 8; ++e) v[e] += (float)rv[e];
+            }
+            if (accumulate) {
+              const bf16x8_t cv = *reinterpret_cast<const bf16x8_t*>(C + row * ldc + col);
+#pragma unroll
+              for (int e = 0; e < 8; ++e) v[e] += (float)cv[e];
+            }
+            bf16x8_t o;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) o[e] = (bf16_t)v[e];
+            *reinterpret_cast<bf16x8_t*>(C + row * ldc + col) = o;
+          } else {
+            for (int e = 0; e < 8 && col + e < N; ++e) {
+              float x = v[e];
+              if (R) x += (float)R[row * ldr + col + e];
+              if (accumulate) x += (float)C[row * ldc + col + e];
+              C[row * ldc + col + e] = (bf16_t)x;
+            }
+          }
+        }
+      }
+      __builtin_amdgcn_s_waitcnt(0xc07f);
+      __builtin_amdgcn_wave_barrier();
+    }
+  }
+}
+
+template <int MODE, bool C_F32>
+int launch_t2(int64_t M, int64_t N, int64_t K, const void* A, int64_t lda, const void* B, int64_t ldb, void* C, int64_t ldc,
+              int accumulate, const void* R, int64_t ldr, hipStream_t st) {
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute((const void*)gemm_dlds_kernel<MODE, C_F32>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLds2);
+    if (e != hipSuccess) return (int)e;
+    attr_set = true;
+  }
+  const int tiles_m = (int)((M + BM - 1) / BM), tiles_n = (int)((N + BN - 1) / BN);
+  hipLaunchKernelGGL((gemm_dlds_kernel<MODE, C_F32>), dim3((unsigned)(tiles_m * tiles_n)), dim3(kThreads), kLds2, st, M, N, K,
+                     (const bf16_t*)A, lda, (const bf16_t*)B, ldb, C, ldc, accumulate, R, ldr, tiles_m, tiles_n);
+  return (int)hipGetLastError();
+}
+
+}  // namespace v2
+
 template <int MODE, bool C_F32>
 int launch_t(int64_t M, int64_t N, int64_t K, const void* A, int64_t lda, const void* B, int64_t ldb, void* C, int64_t ldc,
              int accumulate, const void* R, int64_t ldr, hipStream_t st) {
@@ -271,13 +608,23 @@ bool gemm_mfma_supported(int dtype, int mode, int64_t M, int64_t N, int64_t K, i
 int launch_gemm_mfma(int mode, int64_t M, int64_t N, int64_t K, const void* A, int64_t lda, const void* B, int64_t ldb,
                      void* C, int64_t ldc, int c_dtype, int accumulate, const void* R, int64_t ldr, hipStream_t st) {
   const bool f32 = c_dtype == DT_F32;
+  if (K % v2::BK2 != 0 || K < v2::BK2) {     // the pipelined kernel has no K tail
+    switch (mode) {
+      case GEMM_NT: return f32 ? launch_t<GEMM_NT, true>(M, N, K, A, lda, B, ldb, C, ldc, accumulate, R, ldr, st)
+                               : launch_t<GEMM_NT, false>(M, N, K, A, lda, B, ldb, C, ldc, accumulate, R, ldr, st);
+      case GEMM_NN: return f32 ? launch_t<GEMM_NN, true>(M, N, K, A, lda, B, ldb, C, ldc, accumulate, R, ldr, st)
+                               : launch_t<GEMM_NN, false>(M, N, K, A, lda, B, ldb, C, ldc, accumulate, R, ldr, st);
+      default: return f32 ? launch_t<GEMM_TN, true>(M, N, K, A, lda, B, ldb, C, ldc, accumulate, R, ldr, st)
+                          : launch_t<GEMM_TN, false>(M, N, K, A, lda, B, ldb, C, ldc, accumulate, R, ldr, st);
+    }
+  }
   switch (mode) {
-    case GEMM_NT: return f32 ? launch_t<GEMM_NT, true>(M, N, K, A, lda, B, ldb, C, ldc, accumulate, R, ldr, st)
-                             : launch_t<GEMM_NT, false>(M, N, K, A, lda, B, ldb, C, ldc, accumulate, R, ldr, st);
-    case GEMM_NN: return f32 ? launch_t<GEMM_NN, true>(M, N, K, A, lda, B, ldb, C, ldc, accumulate, R, ldr, st)
-                             : launch_t<GEMM_NN, false>(M, N, K, A, lda, B, ldb, C, ldc, accumulate, R, ldr, st);
-    default: return f32 ? launch_t<GEMM_TN, true>(M, N, K, A, lda, B, ldb, C, ldc, accumulate, R, ldr, st)
-                        : launch_t<GEMM_TN, false>(M, N, K, A, lda, B, ldb, C, ldc, accumulate, R, ldr, st);
+    case GEMM_NT: return f32 ? v2::launch_t2<GEMM_NT, true>(M, N, K, A, lda, B, ldb, C, ldc, accumulate, R, ldr, st)
+                             : v2::launch_t2<GEMM_NT, false>(M, N, K, A, lda, B, ldb, C, ldc, accumulate, R, ldr, st);
+    case GEMM_NN: return f32 ? v2::launch_t2<GEMM_NN, true>(M, N, K, A, lda, B, ldb, C, ldc, accumulate, R, ldr, st)
+                             : v2::launch_t2<GEMM_NN, false>(M, N, K, A, lda, B, ldb, C, ldc, accumulate, R, ldr, st);
+    default: return f32 ? v2::launch_t2<GEMM_TN, true>(M, N, K, A, lda, B, ldb, C, ldc, accumulate, R, ldr, st)
+                        : v2::launch_t2<GEMM_TN, false>(M, N, K, A, lda, B, ldb, C, ldc, accumulate, R, ldr, st);
   }
 }
 
