@@ -97,164 +97,191 @@ __device__ __forceinline__ bf16x8_t pack8(const f32x16_t& x, int t) {
   return p;
 }
 
-// =============================================================================== forward
-// Workgroup: one (batch, head, 128*QSUB query rows); wavefront w owns rows 32*QSUB*w .. +32*QSUB.
-// Keys/values stream through LDS in tiles of 64, double buffered.
-template <int QSUB>
-__global__ void __launch_bounds__(kThreads, 1)
-attn_fwd_kernel(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ o, float* __restrict__ lse, int B, int S, int nh, float scale) {
-  constexpr int BQ = 128 * QSUB, WQ = 32 * QSUB, BKV = 64;
-  constexpr int kTile = BKV * D;   // elements
-  extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
-  bf16_t* lds = reinterpret_cast<bf16_t*>(lds_raw);   // [stage][K tile | V tile]
+// ---- direct global -> LDS tile loads ----------------------------------------------------------------
+typedef __attribute__((address_space(3))) unsigned char lds_u8_t;
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, hh = lane >> 5;
+// s_waitcnt vmcnt(n) with the other counters left alone (gfx9 encoding: vmcnt[3:0] | expcnt<<4 | lgkmcnt<<8 | vmcnt[5:4]<<14)
+template <int N> __device__ __forceinline__ void wait_vmcnt() {
+  __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (15 << 8) | ((N >> 4) << 14));
+}
+
+// 16 bytes per lane from global memory (64-bit scalar base + 32-bit per-lane byte offset) straight
+// into LDS at lds_addr + 16 * lane (lds_addr wavefront-uniform).  Inline assembly so that the
+// compiler's wait-count insertion does not see the load: it would put s_waitcnt vmcnt(0) in front
+// of every transposing LDS read that follows.  The kernels order these loads themselves (vmcnt
+// wait + workgroup barrier before a stage is read, barrier after its last read before a refill).
+__device__ __forceinline__ void lds_dma16(uint64_t base, unsigned off, unsigned lds_addr) {
+  asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(off), "s"(base), "s"(lds_addr));
+}
+// 4 bytes per lane, same addressing (LDS destination lds_addr + 4 * lane)
+__device__ __forceinline__ void lds_dma4(uint64_t base, unsigned off, unsigned lds_addr) {
+  asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dword %0, %1" ::"v"(off), "s"(base), "s"(lds_addr));
+}
+// workgroup barrier that also tells the compiler that LDS changed behind its back
+__device__ __forceinline__ void stage_barrier() {
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+}
+
+constexpr int kWaves8 = 8, kThreads8 = 512;
+constexpr int kTileBytes = 64 * D * 2;      // a [64][128] bf16 tile: 16 KiB
+
+// This wavefront's share (2 of the 16 one-KiB pieces) of a [64][128] tile load: rows row0 .. row0+63
+// of a row-major matrix (row stride ld_bytes, rows clamped to limit-1) into the swizzled LDS tile at
+// lds_tile.  Piece j holds rows 4j..4j+3; lane l writes slot l&15 of row 4j + (l>>4), and slot s of
+// row r holds chunk s ^ swizzle(r): the lane fetches the chunk that belongs where it writes.
+__device__ __forceinline__ void tile_dma(uint64_t base, unsigned ld_bytes, int row0, int limit, unsigned lds_tile, int lane, int wave) {
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int j = wave + 8 * i;
+    const int r = 4 * j + (lane >> 4);
+    const int c = swz(r, lane & 15);
+    int rg = row0 + r;
+    rg = rg < limit ? rg : limit - 1;
+    lds_dma16(base, (unsigned)rg * ld_bytes + c * 16, lds_tile + j * 1024);
+  }
+}
+
+// =============================================================================== forward
+// Workgroup: 8 wavefronts (two per SIMD, so one's softmax arithmetic overlaps the other's MFMAs),
+// one (batch, head, 256 query rows); wavefront w owns rows 32w .. 32w+31.  Keys/values stream
+// through a 4-stage LDS ring of 64-key tiles filled by direct global->LDS loads issued three
+// tiles ahead; one workgroup barrier per tile.
+//
+// Online softmax in the exp2 domain.  The running maximum of a row is only raised when a tile
+// exceeds it by more than kMaxSlack (in log2 units): until then the probabilities of the tile are
+// taken relative to the stale maximum (they stay below 2^kMaxSlack, harmless in fp32 / bf16) and
+// the 64 accumulator registers need no rescaling.  The final division by the row sum makes the
+// result independent of which maximum was used.
+constexpr float kMaxSlack = 8.0f;
+
+__global__ void __launch_bounds__(kThreads8, 1)
+attn_fwd_kernel(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ o, float* __restrict__ lse, int B, int S, int nh, float scale) {
+  constexpr int BQ = 256, WQ = 32, BKV = 64, NS = 4;
+  constexpr int kStage = 2 * kTileBytes;   // K tile | V tile
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
+  const unsigned lds0 = (unsigned)(size_t)(const lds_u8_t*)lds_raw;
+
+  const int tid = threadIdx.x, lane = tid & 63, hh = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int nqt = (S + BQ - 1) / BQ;
   const int bh = blockIdx.x % (B * nh);
   const int qt = nqt - 1 - blockIdx.x / (B * nh);      // longest rows first
   const int b = bh / nh, h = bh % nh;
   const int64_t H = (int64_t)nh * D, ld = 3 * H;
   const bf16_t* qbase = qkv + (int64_t)b * S * ld + (int64_t)h * D;
-  const bf16_t* kbase = qbase + H;
-  const bf16_t* vbase = qbase + 2 * H;
+  const uint64_t kbase = (uint64_t)(qbase + H), vbase = (uint64_t)(qbase + 2 * H);
+  const unsigned ldb = (unsigned)(ld * 2);
   const int q0 = qt * BQ, q0w = q0 + wave * WQ;
   const float c = scale * kLog2e;
 
-  // Q as B operands, straight from global memory
-  bf16x8_t qf[QSUB][8];
-#pragma unroll
-  for (int qs = 0; qs < QSUB; ++qs) {
-    int row = q0w + qs * 32 + (lane & 31);
-    if (row >= S) row = S - 1;
-#pragma unroll
-    for (int ks = 0; ks < 8; ++ks)
-      qf[qs][ks] = *reinterpret_cast<const bf16x8_t*>(qbase + (int64_t)row * ld + 16 * ks + 8 * hh);
-  }
-
-  f32x16_t oacc[QSUB][4];
-  float m[QSUB], l[QSUB];
-#pragma unroll
-  for (int qs = 0; qs < QSUB; ++qs) {
-    m[qs] = -INFINITY; l[qs] = 0.f;
-#pragma unroll
-    for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) oacc[qs][dt][r] = 0.f;
-  }
-
   const int kv_end = (q0 + BQ < S) ? q0 + BQ : S;
   const int nkv = (kv_end + BKV - 1) / BKV;
-  u32x4_t rk[4], rv[4];
-  tile_load(rk, kbase, ld, 0, S, tid);
-  tile_load(rv, vbase, ld, 0, S, tid);
-  tile_store(lds, rk, tid);
-  tile_store(lds + kTile, rv, tid);
-  __syncthreads();
+  auto issue = [&](int t) {
+    const unsigned st = lds0 + (t & (NS - 1)) * kStage;
+    tile_dma(kbase, ldb, t * BKV, S, st, lane, wave);
+    tile_dma(vbase, ldb, t * BKV, S, st + kTileBytes, lane, wave);
+  };
+  for (int t = 0; t < NS - 1 && t < nkv; ++t) issue(t);
+
+  // Q as B operands, straight from global memory
+  bf16x8_t qf[8];
+  {
+    int row = q0w + (lane & 31);
+    if (row >= S) row = S - 1;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) qf[ks] = *reinterpret_cast<const bf16x8_t*>(qbase + (int64_t)row * ld + 16 * ks + 8 * hh);
+  }
+  f32x16_t oacc[4];
+  float m = -INFINITY, l = 0.f;      // running maximum (scaled, log2 domain) and sum of this lane's half of the keys
+#pragma unroll
+  for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) oacc[dt][r] = 0.f;
+  const int qidx = q0w + (lane & 31);
 
   for (int j = 0; j < nkv; ++j) {
-    const bf16_t* sk = lds + (j & 1) * 2 * kTile;
-    const bf16_t* sv = sk + kTile;
-    const bool more = j + 1 < nkv;
-    if (more) {
-      tile_load(rk, kbase, ld, (j + 1) * BKV, S, tid);
-      tile_load(rv, vbase, ld, (j + 1) * BKV, S, tid);
-    }
+    // tile j has landed (each wavefront waits for its own pieces, the barrier collects them); the
+    // barrier also says every wavefront is done with tile j-1, whose stage tile j+3 goes into
+    const int ahead = nkv - 1 - j;
+    if (ahead >= 2) wait_vmcnt<8>(); else if (ahead == 1) wait_vmcnt<4>(); else wait_vmcnt<0>();
+    stage_barrier();
+    if (j + NS - 1 < nkv) issue(j + NS - 1);
     const int kv0 = j * BKV;
-    if (kv0 <= q0w + WQ - 1) {                        // some key of the tile is visible to this wavefront
-      f32x16_t s[QSUB][2];
+    if (kv0 > q0w + WQ - 1) continue;                  // no key of the tile is visible to this wavefront
+    const bf16_t* sk = reinterpret_cast<const bf16_t*>(lds_raw + (j & (NS - 1)) * kStage);
+    const bf16_t* sv = sk + 64 * D;
+
+    f32x16_t s[2];
 #pragma unroll
-      for (int qs = 0; qs < QSUB; ++qs)
+    for (int kb = 0; kb < 2; ++kb) {
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
+      for (int r = 0; r < 16; ++r) s[kb][r] = 0.f;
 #pragma unroll
-          for (int r = 0; r < 16; ++r) s[qs][kb][r] = 0.f;
+      for (int ks = 0; ks < 8; ++ks) s[kb] = mfma(frag_nat(sk, kb * 32, ks, lane), qf[ks], s[kb]);
+    }
+    if (kv0 + BKV - 1 > q0w) {                         // tile crosses the diagonal (or the end of the sequence)
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-        for (int ks = 0; ks < 8; ++ks) {
-          const bf16x8_t kf = frag_nat(sk, kb * 32, ks, lane);
-#pragma unroll
-          for (int qs = 0; qs < QSUB; ++qs) s[qs][kb] = mfma(kf, qf[qs][ks], s[qs][kb]);
+        for (int r = 0; r < 16; ++r) {
+          const int kv = kv0 + kb * 32 + 8 * (r >> 2) + 4 * hh + (r & 3);
+          s[kb][r] = kv > qidx ? -INFINITY : s[kb][r];
         }
-      const bool need_mask = kv0 + BKV - 1 > q0w;
-      bf16x8_t pf[QSUB][2][2];
+    }
+    float mx = fmaxf(s[0][0], s[1][0]);
 #pragma unroll
-      for (int qs = 0; qs < QSUB; ++qs) {
-        const int qidx = q0w + qs * 32 + (lane & 31);
-        float mx = -INFINITY;
+    for (int r = 1; r < 16; ++r) mx = fmaxf(mx, fmaxf(s[0][r], s[1][r]));
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64)) * c;
+    if (__builtin_amdgcn_ballot_w64(mx > m + kMaxSlack) != 0) {    // wavefront-uniform: some row's maximum moved far
+      const float m_new = fmaxf(m, mx);
+      const float alpha = fast_exp2(m - m_new);        // m = -inf on the first tile: alpha = 0, the accumulators are 0
+      m = m_new;
+      l *= alpha;
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
+      for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            float t = s[qs][kb][r] * c;
-            if (need_mask) {
-              const int kv = kv0 + kb * 32 + 8 * (r >> 2) + 4 * hh + (r & 3);
-              t = kv > qidx ? -INFINITY : t;
-            }
-            s[qs][kb][r] = t;
-            mx = fmaxf(mx, t);
-          }
-        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-        const float m_new = fmaxf(m[qs], mx);
-        const float alpha = fast_exp2(m[qs] - m_new);
-        m[qs] = m_new;
-        float rs = 0.f;
+        for (int r = 0; r < 16; ++r) oacc[dt][r] *= alpha;
+    }
+    float rs = 0.f;
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
+    for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            const float p = fast_exp2(s[qs][kb][r] - m_new);
-            s[qs][kb][r] = p;
-            rs += p;
-          }
-        l[qs] = l[qs] * alpha + rs;
-#pragma unroll
-        for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) oacc[qs][dt][r] *= alpha;
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-          for (int t = 0; t < 2; ++t) pf[qs][kb][t] = pack8(s[qs][kb], t);
+      for (int r = 0; r < 16; ++r) {
+        const float p = fast_exp2(__builtin_fmaf(s[kb][r], c, -m));
+        s[kb][r] = p;
+        rs += p;
       }
+    l += rs;
 #pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
+    for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-        for (int t = 0; t < 2; ++t)
+      for (int t = 0; t < 2; ++t) {
+        const bf16x8_t pf = pack8(s[kb], t);
 #pragma unroll
-          for (int dt = 0; dt < 4; ++dt) {
-            const bf16x8_t vf = frag_tr(sv, kb * 32, t, dt * 32, lane);
-#pragma unroll
-            for (int qs = 0; qs < QSUB; ++qs) oacc[qs][dt] = mfma(vf, pf[qs][kb][t], oacc[qs][dt]);
-          }
-    }
-    if (more) {
-      bf16_t* dk = lds + ((j + 1) & 1) * 2 * kTile;
-      tile_store(dk, rk, tid);
-      tile_store(dk + kTile, rv, tid);
-    }
-    __syncthreads();
+        for (int dt = 0; dt < 4; ++dt) oacc[dt] = mfma(frag_tr(sv, kb * 32, t, dt * 32, lane), pf, oacc[dt]);
+      }
   }
+  __syncthreads();          // every wavefront is done with the ring: it becomes the output staging area
 
   // ---- epilogue: O^T accumulators -> [q][136] bf16 staging in LDS -> coalesced rows of o
   constexpr int OLD = 136;
-  bf16_t* ob = lds + wave * (WQ * OLD);
-#pragma unroll
-  for (int qs = 0; qs < QSUB; ++qs) {
-    const float lsum = l[qs] + __shfl_xor(l[qs], 32, 64);
+  bf16_t* ob = reinterpret_cast<bf16_t*>(lds_raw) + wave * (WQ * OLD);
+  {
+    const float lsum = l + __shfl_xor(l, 32, 64);
     const float inv = 1.0f / lsum;
-    const int qrow = qs * 32 + (lane & 31);
+    const int qrow = lane & 31;
 #pragma unroll
     for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
       for (int r4 = 0; r4 < 4; ++r4) {
         bf16x4_t pk;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) pk[e] = (bf16_t)(oacc[qs][dt][4 * r4 + e] * inv);
+        for (int e = 0; e < 4; ++e) pk[e] = (bf16_t)(oacc[dt][4 * r4 + e] * inv);
         *reinterpret_cast<bf16x4_t*>(ob + qrow * OLD + dt * 32 + 8 * r4 + 4 * hh) = pk;
       }
-    const int qidx = q0w + qrow;
-    if (hh == 0 && qidx < S) lse[((int64_t)b * nh + h) * S + qidx] = m[qs] * kLn2 + logf(lsum);
+    if (hh == 0 && qidx < S) lse[((int64_t)b * nh + h) * S + qidx] = m * kLn2 + logf(lsum);
   }
   __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0): this wavefront's LDS writes are done
   __builtin_amdgcn_wave_barrier();
@@ -554,26 +581,26 @@ attn_bwd_dq_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dO
   for (int qs = 0; qs < QSUB; ++qs) store_rows_T(dq[qs], scale, stage, dqout, ld, q0w + qs * 32, S, lane);
 }
 
-template <int QSUB>
-int launch_fwd_t(int B, int S, int nh, const void* qkv, void* o, float* lse, hipStream_t st) {
-  constexpr int BQ = 128 * QSUB;
-  constexpr size_t lds_main = 2 * 2 * 64 * D * sizeof(bf16_t);
-  constexpr size_t lds_epi = 4 * 32 * QSUB * 136 * sizeof(bf16_t);
-  constexpr size_t lds = lds_main > lds_epi ? lds_main : lds_epi;
-  hipError_t e = hipFuncSetAttribute((const void*)attn_fwd_kernel<QSUB>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+int launch_fwd(int B, int S, int nh, const void* qkv, void* o, float* lse, hipStream_t st) {
+  constexpr int BQ = 256;
+  constexpr size_t lds = 4 * 2 * kTileBytes;      // the ring; the output staging (8 x 32 x 136 bf16) fits inside
+  static_assert(lds >= 8 * 32 * 136 * sizeof(bf16_t), "staging area");
+  hipError_t e = hipFuncSetAttribute((const void*)attn_fwd_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
   if (e != hipSuccess) return (int)e;
   const int nqt = (S + BQ - 1) / BQ;
   const float scale = 1.0f / sqrtf((float)D);
-  hipLaunchKernelGGL((attn_fwd_kernel<QSUB>), dim3((unsigned)(nqt * B * nh)), dim3(kThreads), lds, st, (const bf16_t*)qkv, (bf16_t*)o, lse, B, S, nh, scale);
+  hipLaunchKernelGGL(attn_fwd_kernel, dim3((unsigned)(nqt * B * nh)), dim3(kThreads8), lds, st, (const bf16_t*)qkv, (bf16_t*)o, lse, B, S, nh, scale);
   return (int)hipGetLastError();
 }
 
 }  // namespace
 
-bool attn_mfma_supported(int dtype, int S, int d) { return dtype == DT_BF16 && d == D && S >= 1; }
+bool attn_mfma_supported(int dtype, int S, int nh, int d) {
+  return dtype == DT_BF16 && d == D && S >= 1 && nh >= 1 && (int64_t)S * 3 * nh * D * 2 < ((int64_t)1 << 32);
+}
 
 int launch_attn_fwd_mfma(int B, int S, int nh, const void* qkv, void* o, float* lse, hipStream_t st) {
-  return launch_fwd_t<2>(B, S, nh, qkv, o, lse, st);
+  return launch_fwd(B, S, nh, qkv, o, lse, st);
 }
 
 int launch_attn_bwd_mfma(int B, int S, int nh, const void* qkv, const void* dO, const float* lse, const float* Dv, void* dqkv, hipStream_t st) {

@@ -76,7 +76,7 @@ static int make_plan(const taw_layer_desc* d, Plan* p) {
   const int64_t T = (int64_t)d->B * d->S;
   p->mfma_gemm = d->dtype == TAW_BF16 && d->H % 8 == 0 && d->I % 8 == 0 &&
                  gemm_mfma_supported(DT_BF16, GEMM_NT, T, 3 * (int64_t)d->H, d->H, d->H, d->H, 3 * (int64_t)d->H, DT_BF16, 0);
-  p->mfma_attn = attn_mfma_supported(d->dtype, d->S, d->head_dim);
+  p->mfma_attn = attn_mfma_supported(d->dtype, d->S, d->n_heads, d->head_dim);
   if (!rmsnorm_supported(d->dtype, d->H))
     return fail(TAW_ERR_UNSUPPORTED, "RMSNorm kernels hold a row in registers: H=%d is too wide for them", d->H);
   if (!p->mfma_attn && !attn_generic_supported(d->S, d->head_dim))
@@ -392,7 +392,7 @@ static int check_attn(int32_t dtype, int32_t B, int32_t S, int32_t nh, int32_t d
   int rc = check_dtype(dtype);
   if (rc) return rc;
   if (B <= 0 || S <= 0 || nh <= 0 || d <= 0 || d % 2) return fail(TAW_ERR_SHAPE, "bad attention shape (B=%d S=%d n_heads=%d head_dim=%d)", B, S, nh, d);
-  const bool can = attn_mfma_supported(dtype, S, d);
+  const bool can = attn_mfma_supported(dtype, S, nh, d);
   if (impl == TAW_IMPL_MFMA && !can) return fail(TAW_ERR_UNSUPPORTED, "MFMA attention needs bf16 and head_dim 128");
   *use_mfma = can && impl != TAW_IMPL_GENERIC;
   if (!*use_mfma && !attn_generic_supported(S, d)) return fail(TAW_ERR_UNSUPPORTED, "generic attention kernel takes S <= 4096");

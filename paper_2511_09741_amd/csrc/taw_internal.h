@@ -57,7 +57,8 @@ bool gemm_mfma_supported(int dtype, int mode, int64_t M, int64_t N, int64_t K, i
 int launch_gemm_mfma(int mode, int64_t M, int64_t N, int64_t K, const void* A, int64_t lda, const void* B,
                      int64_t ldb, void* C, int64_t ldc, int c_dtype, int accumulate, const void* R,
                      int64_t ldr, hipStream_t st);
-bool attn_mfma_supported(int dtype, int S, int d);
+// bf16, head_dim 128, and S * 3 * n_heads * head_dim * 2 bytes below 4 GiB (32-bit row offsets inside one batch element)
+bool attn_mfma_supported(int dtype, int S, int nh, int d);
 int launch_attn_fwd_mfma(int B, int S, int nh, const void* qkv, void* o, float* lse, hipStream_t st);
 int launch_attn_bwd_mfma(int B, int S, int nh, const void* qkv, const void* dO, const float* lse,
                          const float* D, void* dqkv, hipStream_t st);
