@@ -323,22 +323,22 @@ __device__ __forceinline__ void store_rows_T(const f32x16_t (&acc)[4], float mul
 }
 
 // =============================================================================== backward: dK, dV
-// Workgroup: one (batch, head, 128 keys); wavefront w owns keys 32w..32w+31 and keeps their K and V
-// rows in registers as B operands.  Query rows stream through LDS in blocks of 64 (Q and dO tiles,
-// plus lse and D), from the diagonal to the end of the sequence.
+// Workgroup: 8 wavefronts, one (batch, head, 256 keys); wavefront w owns keys 32w..32w+31 and keeps
+// their K and V rows in registers as B operands.  Query rows stream through a 4-stage LDS ring in
+// blocks of 64 (Q and dO tiles plus the rows' lse and D), from the diagonal to the end of the
+// sequence, filled by direct global->LDS loads three blocks ahead.
 //   S = Q K^T;  P = exp(S/sqrt(d) - lse);  dP = dO V^T;  dS = P (dP - D)
 //   dV^T += dO^T P;   dK^T += Q^T dS  (scaled by 1/sqrt(d) at the end)
-__global__ void __launch_bounds__(kThreads, 1)
+__global__ void __launch_bounds__(kThreads8, 1)
 attn_bwd_dkv_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dO, const float* __restrict__ lse,
                     const float* __restrict__ Dsum, bf16_t* __restrict__ dqkv, int B, int S, int nh, float scale) {
-  constexpr int BKVW = 128, BQ = 64;
-  constexpr int kTile = BQ * D;
-  constexpr int kStage = 2 * kTile + 2 * 2 * BQ;   // Q tile, dO tile (bf16) + lse2[64], D[64] (fp32 = 2 bf16 slots each)
+  constexpr int BKVW = 256, BQ = 64, NS = 4;
+  constexpr int kStage = 2 * kTileBytes + 2 * BQ * 4;   // Q tile | dO tile | lse[64] | D[64]
   extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
-  bf16_t* lds = reinterpret_cast<bf16_t*>(lds_raw);
+  const unsigned lds0 = (unsigned)(size_t)(const lds_u8_t*)lds_raw;
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, hh = lane >> 5;
-  const int nkt = (S + BKVW - 1) / BKVW;
+  const int tid = threadIdx.x, lane = tid & 63, hh = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int bh = blockIdx.x % (B * nh);
   const int kt = blockIdx.x / (B * nh);                 // early key tiles see the most queries: they go first
   const int b = bh / nh, h = bh % nh;
@@ -346,12 +346,26 @@ attn_bwd_dkv_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ d
   const bf16_t* qbase = qkv + (int64_t)b * S * ld + (int64_t)h * D;
   const bf16_t* kbase = qbase + H;
   const bf16_t* vbase = qbase + 2 * H;
-  const bf16_t* dobase = dO + (int64_t)b * S * H + (int64_t)h * D;
-  const float* lbase = lse + ((int64_t)b * nh + h) * S;
-  const float* dbase = Dsum + ((int64_t)b * nh + h) * S;
+  const uint64_t qb64 = (uint64_t)qbase, do64 = (uint64_t)(dO + (int64_t)b * S * H + (int64_t)h * D);
+  const uint64_t l64 = (uint64_t)(lse + ((int64_t)b * nh + h) * S), d64 = (uint64_t)(Dsum + ((int64_t)b * nh + h) * S);
+  const unsigned ldb = (unsigned)(ld * 2), ldob = (unsigned)(H * 2);
   const int kv0 = kt * BKVW, kv0w = kv0 + wave * 32;
   const float c = scale * kLog2e;
-  (void)nkt;
+
+  const int jb = kv0 / BQ, je = (S + BQ - 1) / BQ;      // query blocks jb .. je-1
+  const int nblk = je - jb;
+  auto issue = [&](int t) {
+    const unsigned st = lds0 + (t & (NS - 1)) * kStage;
+    const int row0 = (jb + t) * BQ;
+    tile_dma(qb64, ldb, row0, S, st, lane, wave);
+    tile_dma(do64, ldob, row0, S, st + kTileBytes, lane, wave);
+    if (wave < 2) {                                     // wavefront 0: the block's lse; wavefront 1: its D
+      int row = row0 + lane;
+      row = row < S ? row : S - 1;
+      lds_dma4(wave == 0 ? l64 : d64, (unsigned)row * 4u, st + 2 * kTileBytes + wave * (BQ * 4));
+    }
+  };
+  for (int t = 0; t < NS - 1 && t < nblk; ++t) issue(t);
 
   bf16x8_t kf[8], vf[8];
   {
@@ -368,89 +382,65 @@ attn_bwd_dkv_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ d
   for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
     for (int r = 0; r < 16; ++r) { dk[dt][r] = 0.f; dv[dt][r] = 0.f; }
+  const int kvi = kv0w + (lane & 31);
 
-  const int jb = kv0 / BQ, je = (S + BQ - 1) / BQ;      // query blocks jb .. je-1
-  u32x4_t rq[4], rdo[4];
-  float rl = 0.f, rd = 0.f;                              // threads 0..63 stage lse2 / D of the block
-  auto stage_load = [&](int j) {
-    tile_load(rq, qbase, ld, j * BQ, S, tid);
-    tile_load(rdo, dobase, H, j * BQ, S, tid);
-    if (tid < BQ) {
-      int row = j * BQ + tid;
-      if (row >= S) row = S - 1;
-      rl = lbase[row] * kLog2e;
-      rd = dbase[row];
-    }
-  };
-  auto stage_store = [&](int st) {
-    bf16_t* base = lds + st * kStage;
-    tile_store(base, rq, tid);
-    tile_store(base + kTile, rdo, tid);
-    float* f = reinterpret_cast<float*>(base + 2 * kTile);
-    if (tid < BQ) { f[tid] = rl; f[BQ + tid] = rd; }
-  };
-  if (jb < je) {
-    stage_load(jb);
-    stage_store(0);
-  }
-  __syncthreads();
-
-  for (int j = jb; j < je; ++j) {
-    const bf16_t* sq = lds + ((j - jb) & 1) * kStage;
-    const bf16_t* sdo = sq + kTile;
-    const float* sl = reinterpret_cast<const float*>(sq + 2 * kTile);
+  for (int t = 0; t < nblk; ++t) {
+    const int ahead = nblk - 1 - t;
+    if (wave < 2) { if (ahead >= 2) wait_vmcnt<10>(); else if (ahead == 1) wait_vmcnt<5>(); else wait_vmcnt<0>(); }
+    else { if (ahead >= 2) wait_vmcnt<8>(); else if (ahead == 1) wait_vmcnt<4>(); else wait_vmcnt<0>(); }
+    stage_barrier();
+    if (t + NS - 1 < nblk) issue(t + NS - 1);
+    const int qb0 = (jb + t) * BQ;
+    if (qb0 + BQ - 1 < kv0w) continue;                   // no query of the block sees this wavefront's keys
+    const unsigned char* stg = lds_raw + (t & (NS - 1)) * kStage;
+    const bf16_t* sq = reinterpret_cast<const bf16_t*>(stg);
+    const bf16_t* sdo = sq + 64 * D;
+    const float* sl = reinterpret_cast<const float*>(stg + 2 * kTileBytes);
     const float* sd = sl + BQ;
-    const bool more = j + 1 < je;
-    if (more) stage_load(j + 1);
-    const int qb0 = j * BQ;
-    if (qb0 + BQ - 1 >= kv0w) {                          // some query of the block sees this wavefront's keys
 #pragma unroll
-      for (int qb = 0; qb < 2; ++qb) {
-        const int qrow0 = qb0 + qb * 32;
-        if (qrow0 + 31 < kv0w) continue;                 // wavefront-uniform
-        f32x16_t sacc, pacc;
+    for (int qb = 0; qb < 2; ++qb) {
+      const int qrow0 = qb0 + qb * 32;
+      if (qrow0 + 31 < kv0w) continue;                   // wavefront-uniform
+      f32x16_t sacc, pacc;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) { sacc[r] = 0.f; pacc[r] = 0.f; }
+      for (int r = 0; r < 16; ++r) { sacc[r] = 0.f; pacc[r] = 0.f; }
 #pragma unroll
-        for (int ks = 0; ks < 8; ++ks) {
-          sacc = mfma(frag_nat(sq, qb * 32, ks, lane), kf[ks], sacc);
-          pacc = mfma(frag_nat(sdo, qb * 32, ks, lane), vf[ks], pacc);
-        }
-        const bool need_mask = (qrow0 < kv0w + 31) || (qrow0 + 31 >= S);
-        const int kvi = kv0w + (lane & 31);
+      for (int ks = 0; ks < 8; ++ks) {
+        sacc = mfma(frag_nat(sq, qb * 32, ks, lane), kf[ks], sacc);
+        pacc = mfma(frag_nat(sdo, qb * 32, ks, lane), vf[ks], pacc);
+      }
+      const bool need_mask = (qrow0 < kv0w + 31) || (qrow0 + 31 >= S);
 #pragma unroll
-        for (int r4 = 0; r4 < 4; ++r4) {
-          const int rbase = qb * 32 + 8 * r4 + 4 * hh;
-          const f32x4_t l4 = *reinterpret_cast<const f32x4_t*>(sl + rbase);
-          const f32x4_t d4 = *reinterpret_cast<const f32x4_t*>(sd + rbase);
+      for (int r4 = 0; r4 < 4; ++r4) {
+        const int rbase = qb * 32 + 8 * r4 + 4 * hh;
+        const f32x4_t l4 = *reinterpret_cast<const f32x4_t*>(sl + rbase);
+        const f32x4_t d4 = *reinterpret_cast<const f32x4_t*>(sd + rbase);
 #pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            const int r = 4 * r4 + e;
-            float p = fast_exp2(sacc[r] * c - l4[e]);
-            if (need_mask) {
-              const int qi = qb0 + rbase + e;
-              p = (kvi > qi || qi >= S) ? 0.f : p;
-            }
-            sacc[r] = p;
-            pacc[r] = p * (pacc[r] - d4[e]);
+        for (int e = 0; e < 4; ++e) {
+          const int r = 4 * r4 + e;
+          float p = fast_exp2(__builtin_fmaf(sacc[r], c, -l4[e] * kLog2e));
+          if (need_mask) {
+            const int qi = qb0 + rbase + e;
+            p = (kvi > qi || qi >= S) ? 0.f : p;
           }
+          sacc[r] = p;
+          pacc[r] = p * (pacc[r] - d4[e]);
         }
+      }
 #pragma unroll
-        for (int t = 0; t < 2; ++t) {
-          const bf16x8_t pb = pack8(sacc, t), dsb = pack8(pacc, t);
+      for (int tt = 0; tt < 2; ++tt) {
+        const bf16x8_t pb = pack8(sacc, tt), dsb = pack8(pacc, tt);
 #pragma unroll
-          for (int dt = 0; dt < 4; ++dt) {
-            dv[dt] = mfma(frag_tr(sdo, qb * 32, t, dt * 32, lane), pb, dv[dt]);
-            dk[dt] = mfma(frag_tr(sq, qb * 32, t, dt * 32, lane), dsb, dk[dt]);
-          }
+        for (int dt = 0; dt < 4; ++dt) {
+          dv[dt] = mfma(frag_tr(sdo, qb * 32, tt, dt * 32, lane), pb, dv[dt]);
+          dk[dt] = mfma(frag_tr(sq, qb * 32, tt, dt * 32, lane), dsb, dk[dt]);
         }
       }
     }
-    if (more) stage_store((j + 1 - jb) & 1);
-    __syncthreads();
   }
+  __syncthreads();          // the ring becomes the output staging area
 
-  bf16_t* stage = lds + wave * (32 * 136);
+  bf16_t* stage = reinterpret_cast<bf16_t*>(lds_raw) + wave * (32 * 136);
   bf16_t* dkout = dqkv + (int64_t)b * S * ld + H + (int64_t)h * D;
   bf16_t* dvout = dkout + H;
   store_rows_T(dk, scale, stage, dkout, ld, kv0w, S, lane);
@@ -458,127 +448,103 @@ attn_bwd_dkv_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ d
 }
 
 // =============================================================================== backward: dQ
-// Workgroup: one (batch, head, 128*QSUB query rows); wavefront w owns 32*QSUB of them and keeps their
-// Q and dO rows in registers as B operands.  Keys/values stream through LDS in tiles of 64 up to the
-// diagonal.   S^T = K Q^T;  P^T = exp(S^T/sqrt(d) - lse);  dP^T = V dO^T;  dS^T = P^T (dP^T - D);
+// Same workgroup shape and K/V ring as the forward: 8 wavefronts, 256 query rows, wavefront w owns
+// rows 32w..32w+31 and keeps their Q and dO rows in registers as B operands.
+//   S^T = K Q^T;  P^T = exp(S^T/sqrt(d) - lse);  dP^T = V dO^T;  dS^T = P^T (dP^T - D);
 //   dQ^T += K^T dS^T  (scaled by 1/sqrt(d) at the end)
-template <int QSUB>
-__global__ void __launch_bounds__(kThreads, 1)
+__global__ void __launch_bounds__(kThreads8, 1)
 attn_bwd_dq_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dO, const float* __restrict__ lse,
                    const float* __restrict__ Dsum, bf16_t* __restrict__ dqkv, int B, int S, int nh, float scale) {
-  constexpr int BQ = 128 * QSUB, WQ = 32 * QSUB, BKV = 64;
-  constexpr int kTile = BKV * D;
+  constexpr int BQ = 256, WQ = 32, BKV = 64, NS = 4;
+  constexpr int kStage = 2 * kTileBytes;   // K tile | V tile
   extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
-  bf16_t* lds = reinterpret_cast<bf16_t*>(lds_raw);   // [stage][K tile | V tile]
+  const unsigned lds0 = (unsigned)(size_t)(const lds_u8_t*)lds_raw;
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, hh = lane >> 5;
+  const int tid = threadIdx.x, lane = tid & 63, hh = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int nqt = (S + BQ - 1) / BQ;
   const int bh = blockIdx.x % (B * nh);
   const int qt = nqt - 1 - blockIdx.x / (B * nh);
   const int b = bh / nh, h = bh % nh;
   const int64_t H = (int64_t)nh * D, ld = 3 * H;
   const bf16_t* qbase = qkv + (int64_t)b * S * ld + (int64_t)h * D;
-  const bf16_t* kbase = qbase + H;
-  const bf16_t* vbase = qbase + 2 * H;
+  const uint64_t kbase = (uint64_t)(qbase + H), vbase = (uint64_t)(qbase + 2 * H);
   const bf16_t* dobase = dO + (int64_t)b * S * H + (int64_t)h * D;
+  const unsigned ldb = (unsigned)(ld * 2);
   const int q0 = qt * BQ, q0w = q0 + wave * WQ;
   const float c = scale * kLog2e;
 
-  bf16x8_t qf[QSUB][8], dof[QSUB][8];
-  float l2[QSUB], dsum[QSUB];
-  f32x16_t dq[QSUB][4];
-#pragma unroll
-  for (int qs = 0; qs < QSUB; ++qs) {
-    int row = q0w + qs * 32 + (lane & 31);
+  const int kv_end = (q0 + BQ < S) ? q0 + BQ : S;
+  const int nkv = (kv_end + BKV - 1) / BKV;
+  auto issue = [&](int t) {
+    const unsigned st = lds0 + (t & (NS - 1)) * kStage;
+    tile_dma(kbase, ldb, t * BKV, S, st, lane, wave);
+    tile_dma(vbase, ldb, t * BKV, S, st + kTileBytes, lane, wave);
+  };
+  for (int t = 0; t < NS - 1 && t < nkv; ++t) issue(t);
+
+  bf16x8_t qf[8], dof[8];
+  float l2, dsum;
+  f32x16_t dq[4];
+  {
+    int row = q0w + (lane & 31);
     if (row >= S) row = S - 1;
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) {
-      qf[qs][ks] = *reinterpret_cast<const bf16x8_t*>(qbase + (int64_t)row * ld + 16 * ks + 8 * hh);
-      dof[qs][ks] = *reinterpret_cast<const bf16x8_t*>(dobase + (int64_t)row * H + 16 * ks + 8 * hh);
+      qf[ks] = *reinterpret_cast<const bf16x8_t*>(qbase + (int64_t)row * ld + 16 * ks + 8 * hh);
+      dof[ks] = *reinterpret_cast<const bf16x8_t*>(dobase + (int64_t)row * H + 16 * ks + 8 * hh);
     }
-    l2[qs] = lse[((int64_t)b * nh + h) * S + row] * kLog2e;
-    dsum[qs] = Dsum[((int64_t)b * nh + h) * S + row];
+    l2 = lse[((int64_t)b * nh + h) * S + row] * kLog2e;
+    dsum = Dsum[((int64_t)b * nh + h) * S + row];
 #pragma unroll
     for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) dq[qs][dt][r] = 0.f;
+      for (int r = 0; r < 16; ++r) dq[dt][r] = 0.f;
   }
-
-  const int kv_end = (q0 + BQ < S) ? q0 + BQ : S;
-  const int nkv = (kv_end + BKV - 1) / BKV;
-  u32x4_t rk[4], rv[4];
-  tile_load(rk, kbase, ld, 0, S, tid);
-  tile_load(rv, vbase, ld, 0, S, tid);
-  tile_store(lds, rk, tid);
-  tile_store(lds + kTile, rv, tid);
-  __syncthreads();
+  const int qidx = q0w + (lane & 31);
 
   for (int j = 0; j < nkv; ++j) {
-    const bf16_t* sk = lds + (j & 1) * 2 * kTile;
-    const bf16_t* sv = sk + kTile;
-    const bool more = j + 1 < nkv;
-    if (more) {
-      tile_load(rk, kbase, ld, (j + 1) * BKV, S, tid);
-      tile_load(rv, vbase, ld, (j + 1) * BKV, S, tid);
-    }
+    const int ahead = nkv - 1 - j;
+    if (ahead >= 2) wait_vmcnt<8>(); else if (ahead == 1) wait_vmcnt<4>(); else wait_vmcnt<0>();
+    stage_barrier();
+    if (j + NS - 1 < nkv) issue(j + NS - 1);
     const int kv0 = j * BKV;
-    if (kv0 <= q0w + WQ - 1) {
-      const bool need_mask = kv0 + BKV - 1 > q0w;
+    if (kv0 > q0w + WQ - 1) continue;
+    const bf16_t* sk = reinterpret_cast<const bf16_t*>(lds_raw + (j & (NS - 1)) * kStage);
+    const bf16_t* sv = sk + 64 * D;
+    const bool need_mask = kv0 + BKV - 1 > q0w;
 #pragma unroll
-      for (int kb = 0; kb < 2; ++kb) {
-        f32x16_t sacc[QSUB], pacc[QSUB];
+    for (int kb = 0; kb < 2; ++kb) {
+      f32x16_t sacc, pacc;
 #pragma unroll
-        for (int qs = 0; qs < QSUB; ++qs)
+      for (int r = 0; r < 16; ++r) { sacc[r] = 0.f; pacc[r] = 0.f; }
 #pragma unroll
-          for (int r = 0; r < 16; ++r) { sacc[qs][r] = 0.f; pacc[qs][r] = 0.f; }
+      for (int ks = 0; ks < 8; ++ks) {
+        sacc = mfma(frag_nat(sk, kb * 32, ks, lane), qf[ks], sacc);
+        pacc = mfma(frag_nat(sv, kb * 32, ks, lane), dof[ks], pacc);
+      }
 #pragma unroll
-        for (int ks = 0; ks < 8; ++ks) {
-          const bf16x8_t ka = frag_nat(sk, kb * 32, ks, lane);
-          const bf16x8_t va = frag_nat(sv, kb * 32, ks, lane);
-#pragma unroll
-          for (int qs = 0; qs < QSUB; ++qs) {
-            sacc[qs] = mfma(ka, qf[qs][ks], sacc[qs]);
-            pacc[qs] = mfma(va, dof[qs][ks], pacc[qs]);
-          }
+      for (int r = 0; r < 16; ++r) {
+        float p = fast_exp2(__builtin_fmaf(sacc[r], c, -l2));
+        if (need_mask) {
+          const int kv = kv0 + kb * 32 + 8 * (r >> 2) + 4 * hh + (r & 3);
+          p = kv > qidx ? 0.f : p;
         }
-        bf16x8_t dsb[QSUB][2];
+        pacc[r] = p * (pacc[r] - dsum);
+      }
 #pragma unroll
-        for (int qs = 0; qs < QSUB; ++qs) {
-          const int qidx = q0w + qs * 32 + (lane & 31);
+      for (int t = 0; t < 2; ++t) {
+        const bf16x8_t dsb = pack8(pacc, t);
 #pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            float p = fast_exp2(sacc[qs][r] * c - l2[qs]);
-            if (need_mask) {
-              const int kv = kv0 + kb * 32 + 8 * (r >> 2) + 4 * hh + (r & 3);
-              p = kv > qidx ? 0.f : p;
-            }
-            pacc[qs][r] = p * (pacc[qs][r] - dsum[qs]);
-          }
-#pragma unroll
-          for (int t = 0; t < 2; ++t) dsb[qs][t] = pack8(pacc[qs], t);
-        }
-#pragma unroll
-        for (int t = 0; t < 2; ++t)
-#pragma unroll
-          for (int dt = 0; dt < 4; ++dt) {
-            const bf16x8_t kt_ = frag_tr(sk, kb * 32, t, dt * 32, lane);
-#pragma unroll
-            for (int qs = 0; qs < QSUB; ++qs) dq[qs][dt] = mfma(kt_, dsb[qs][t], dq[qs][dt]);
-          }
+        for (int dt = 0; dt < 4; ++dt) dq[dt] = mfma(frag_tr(sk, kb * 32, t, dt * 32, lane), dsb, dq[dt]);
       }
     }
-    if (more) {
-      bf16_t* dk = lds + ((j + 1) & 1) * 2 * kTile;
-      tile_store(dk, rk, tid);
-      tile_store(dk + kTile, rv, tid);
-    }
-    __syncthreads();
   }
+  __syncthreads();          // the ring becomes the output staging area
 
-  bf16_t* stage = lds + wave * (32 * 136);
+  bf16_t* stage = reinterpret_cast<bf16_t*>(lds_raw) + wave * (32 * 136);
   bf16_t* dqout = dqkv + (int64_t)b * S * ld + (int64_t)h * D;
-#pragma unroll
-  for (int qs = 0; qs < QSUB; ++qs) store_rows_T(dq[qs], scale, stage, dqout, ld, q0w + qs * 32, S, lane);
+  store_rows_T(dq, scale, stage, dqout, ld, q0w, S, lane);
 }
 
 int launch_fwd(int B, int S, int nh, const void* qkv, void* o, float* lse, hipStream_t st) {
@@ -606,22 +572,22 @@ int launch_attn_fwd_mfma(int B, int S, int nh, const void* qkv, void* o, float* 
 int launch_attn_bwd_mfma(int B, int S, int nh, const void* qkv, const void* dO, const float* lse, const float* Dv, void* dqkv, hipStream_t st) {
   const float scale = 1.0f / sqrtf((float)D);
   {
-    constexpr size_t lds = 2 * (2 * 64 * D * sizeof(bf16_t) + 2 * 64 * sizeof(float));
+    constexpr size_t lds = 4 * (2 * kTileBytes + 2 * 64 * sizeof(float));
+    static_assert(lds >= 8 * 32 * 136 * sizeof(bf16_t), "staging area");
     hipError_t e = hipFuncSetAttribute((const void*)attn_bwd_dkv_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return (int)e;
-    const int nkt = (S + 127) / 128;
-    hipLaunchKernelGGL(attn_bwd_dkv_kernel, dim3((unsigned)(nkt * B * nh)), dim3(kThreads), lds, st, (const bf16_t*)qkv, (const bf16_t*)dO, lse, Dv,
+    const int nkt = (S + 255) / 256;
+    hipLaunchKernelGGL(attn_bwd_dkv_kernel, dim3((unsigned)(nkt * B * nh)), dim3(kThreads8), lds, st, (const bf16_t*)qkv, (const bf16_t*)dO, lse, Dv,
                        (bf16_t*)dqkv, B, S, nh, scale);
     int rc = (int)hipGetLastError();
     if (rc) return rc;
   }
   {
-    constexpr int QSUB = 1;
-    constexpr size_t lds = 2 * 2 * 64 * D * sizeof(bf16_t);
-    hipError_t e = hipFuncSetAttribute((const void*)attn_bwd_dq_kernel<QSUB>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    constexpr size_t lds = 4 * 2 * kTileBytes;
+    hipError_t e = hipFuncSetAttribute((const void*)attn_bwd_dq_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return (int)e;
-    const int nqt = (S + 128 * QSUB - 1) / (128 * QSUB);
-    hipLaunchKernelGGL((attn_bwd_dq_kernel<QSUB>), dim3((unsigned)(nqt * B * nh)), dim3(kThreads), lds, st, (const bf16_t*)qkv, (const bf16_t*)dO, lse, Dv,
+    const int nqt = (S + 255) / 256;
+    hipLaunchKernelGGL(attn_bwd_dq_kernel, dim3((unsigned)(nqt * B * nh)), dim3(kThreads8), lds, st, (const bf16_t*)qkv, (const bf16_t*)dO, lse, Dv,
                        (bf16_t*)dqkv, B, S, nh, scale);
     return (int)hipGetLastError();
   }
