@@ -471,36 +471,49 @@ gemm_dlds_kernel(int64_t M, int64_t N, int64_t K, const bf16_t* __restrict__ A, 
   for (; kt + 3 < nk; ++kt) step(kt, std::true_type{});
   for (; kt < nk; ++kt) step(kt, std::false_type{});
 
-  // ---- epilogue
+  // ---- epilogue: 32 x 128 accumulator blocks -> fp32 staging in LDS ([32 rows][132] per wavefront)
+  // -> 16-byte accesses that cover whole row segments of C
   const int lcol = lane & 31, lrow = 4 * (lane >> 5);
   if (C_F32) {
     float* C = static_cast<float*>(Cv);
     const float* R = static_cast<const float*>(Rv);
-    const bool full = (m0 + BM <= M) && (n0 + BN <= N);
-    for (int i = 0; i < 4; ++i)
-      for (int j = 0; j < 4; ++j) {
-        const int64_t col = n0 + wn + 32 * j + lcol;
-        const int64_t row0 = m0 + wm + 32 * i + lrow;
-        float* cp = C + row0 * ldc + col;
-        const float* rp = R ? R + row0 * ldr + col : nullptr;
-        f32x16_t v;
-        // the selects below keep acc[][] indexed by compile-time constants
+    constexpr int SLD = 132;
+    float* stg = reinterpret_cast<float*>(lds2) + wave * (32 * SLD);
+    const bool vec_ok = (ldc & 3) == 0 && (!R || (ldr & 3) == 0);
 #pragma unroll
-        for (int ii = 0; ii < 4; ++ii)
+    for (int i = 0; i < 4; ++i) {
 #pragma unroll
-          for (int jj = 0; jj < 4; ++jj)
-            if (ii == i && jj == j) v = acc[ii][jj];
+      for (int j = 0; j < 4; ++j)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int dr = 8 * (r >> 2) + (r & 3);
-          if (full || (row0 + dr < M && col < N)) {
-            float x = v[r];
-            if (rp) x += rp[dr * ldr];
-            if (accumulate) x += cp[dr * ldc];
-            cp[dr * ldc] = x;
+        for (int r = 0; r < 16; ++r) stg[(8 * (r >> 2) + lrow + (r & 3)) * SLD + 32 * j + lcol] = acc[i][j][r];
+      __builtin_amdgcn_s_waitcnt(0xc07f);
+      __builtin_amdgcn_wave_barrier();
+      // 32 rows x 128 cols = 1024 chunks of 4 columns; lane -> (row = idx >> 5, chunk = idx & 31): half a
+      // wavefront covers 512 contiguous bytes of a row
+#pragma unroll
+      for (int it = 0; it < 16; ++it) {
+        const int idx = it * 64 + lane, rr = idx >> 5, ch = idx & 31;
+        const int64_t row = m0 + wm + 32 * i + rr, col = n0 + wn + ch * 4;
+        if (row < M && col < N) {
+          f32x4_t v = *reinterpret_cast<const f32x4_t*>(stg + rr * SLD + ch * 4);
+          float* cp = C + row * ldc + col;
+          if (col + 4 <= N && vec_ok) {
+            if (R) v += *reinterpret_cast<const f32x4_t*>(R + row * ldr + col);
+            if (accumulate) v += *reinterpret_cast<const f32x4_t*>(cp);
+            *reinterpret_cast<f32x4_t*>(cp) = v;
+          } else {
+            for (int e = 0; e < 4 && col + e < N; ++e) {
+              float x = v[e];
+              if (R) x += R[row * ldr + col + e];
+              if (accumulate) x += cp[e];
+              cp[e] = x;
+            }
           }
         }
       }
+      __builtin_amdgcn_s_waitcnt(0xc07f);
+      __builtin_amdgcn_wave_barrier();
+    }
   } else {
     // fp32 staging in LDS ([32 rows][132] per wavefront), then 16-byte coalesced bf16 rows
     bf16_t* C = static_cast<bf16_t*>(Cv);

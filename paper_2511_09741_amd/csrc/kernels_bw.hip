@@ -135,14 +135,39 @@ __global__ void __launch_bounds__(256) rmsnorm_bwd_kernel(const T* __restrict__ 
   for (int c = threadIdx.x; c < H; c += 256) prow[c] = lds_cols[c];
 }
 
-// out[c] (=|+=) sum_p partials[p][c], p ascending
+// out[c] (=|+=) sum_p partials[p][c].  A workgroup owns 64 columns: thread (q = tid & 15, g = tid >> 4)
+// sums rows g, g + 16, ... of columns 4q .. 4q + 3 (16-byte loads, a 256-byte row segment per 16
+// threads), then the 16 row groups are added in a fixed order through LDS: reproducible, no atomics.
 __global__ void __launch_bounds__(256) colsum_kernel(const float* __restrict__ partials, int np, int H,
                                                      float* __restrict__ out, int accumulate) {
-  const int c = blockIdx.x * 256 + threadIdx.x;
-  if (c >= H) return;
-  float s = 0.f;
-  for (int p = 0; p < np; ++p) s += partials[(int64_t)p * H + c];
-  out[c] = accumulate ? out[c] + s : s;
+  __shared__ float red[16][64];
+  const int q = threadIdx.x & 15, g = threadIdx.x >> 4;
+  const int c0 = blockIdx.x * 64 + 4 * q;
+  float s[4] = {0.f, 0.f, 0.f, 0.f};
+  if (c0 + 3 < H && (H & 3) == 0) {
+    for (int p = g; p < np; p += 16) {
+      const f32x4_t v = *reinterpret_cast<const f32x4_t*>(partials + (int64_t)p * H + c0);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) s[j] += v[j];
+    }
+  } else {
+    for (int p = g; p < np; p += 16)
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        if (c0 + j < H) s[j] += partials[(int64_t)p * H + c0 + j];
+  }
+#pragma unroll
+  for (int j = 0; j < 4; ++j) red[g][4 * q + j] = s[j];
+  __syncthreads();
+  if (threadIdx.x < 64) {
+    const int c = blockIdx.x * 64 + threadIdx.x;
+    if (c < H) {
+      float t = 0.f;
+#pragma unroll
+      for (int gg = 0; gg < 16; ++gg) t += red[gg][threadIdx.x];
+      out[c] = accumulate ? out[c] + t : t;
+    }
+  }
 }
 
 // =============================================================================== rotary table
@@ -370,7 +395,7 @@ static int rmsnorm_bwd_dispatch(int64_t T_, int H, const T* dout, const T* z, co
 #undef TAW_RN_BWD
   int e = last_err();
   if (e) return e;
-  hipLaunchKernelGGL(colsum_kernel, dim3((H + 255) / 256), dim3(256), 0, st, partials, grid, H, dgamma, accumulate);
+  hipLaunchKernelGGL(colsum_kernel, dim3((H + 63) / 64), dim3(256), 0, st, partials, grid, H, dgamma, accumulate);
   return last_err();
 }
 
