@@ -65,7 +65,9 @@ int taw_op_attn_fwd(int32_t dtype, int32_t B, int32_t S, int32_t n_heads, int32_
                     void* o, float* lse, int32_t impl, void* stream);
 
 /* Its gradient: dqkv [B*S, 3H] from dO [B*S, H], recomputing the probabilities from qkv and lse.
- * scratch: fp32, B*n_heads*S elements (holds D[t] = dO[t].o[t]). */
+ * scratch: fp32, taw_op_attn_bwd_scratch_floats(B, S, n_heads) elements (holds the row statistics
+ * D[t] = dO[t].o[t] and a rescaled copy of lse, padded per head). */
+size_t taw_op_attn_bwd_scratch_floats(int32_t B, int32_t S, int32_t n_heads);
 int taw_op_attn_bwd(int32_t dtype, int32_t B, int32_t S, int32_t n_heads, int32_t head_dim, const void* qkv,
                     const void* o, const void* dO, const float* lse, void* dqkv, float* scratch,
                     int32_t impl, void* stream);

@@ -56,6 +56,7 @@ _SIGS = {
     "taw_op_gemm": (C.c_int, [_i32, _i32, _i64, _i64, _i64, _vp, _i64, _vp, _i64, _vp, _i64, _i32, _i32, _vp, _i64, _i32, _vp]),
     "taw_op_rmsnorm_fwd": (C.c_int, [_i32, _i64, _i32, _vp, _vp, _f, _vp, _vp, _vp]),
     "taw_op_rmsnorm_bwd_scratch_floats": (_sz, [_i32]),
+    "taw_op_attn_bwd_scratch_floats": (_sz, [_i32, _i32, _i32]),
     "taw_op_rmsnorm_bwd": (C.c_int, [_i32, _i64, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _vp, _vp]),
     "taw_op_rope": (C.c_int, [_i32, _i32, _i32, _i32, _i32, _vp, _i64, _vp, _i32, _vp]),
     "taw_op_swiglu_fwd": (C.c_int, [_i32, _i64, _i32, _vp, _vp, _vp]),
@@ -200,6 +201,10 @@ def taw_op_swiglu_bwd(dtype, T, I, da, gu, dgu, stream=None):
 
 def taw_op_attn_fwd(dtype, B, S, n_heads, head_dim, qkv, o, lse, impl=TAW_IMPL_AUTO, stream=None):
     _check(load().taw_op_attn_fwd(dtype, B, S, n_heads, head_dim, _p(qkv), _p(o), _p(lse), impl, _stream(stream)))
+
+
+def taw_op_attn_bwd_scratch_floats(B, S, n_heads) -> int:
+    return int(load().taw_op_attn_bwd_scratch_floats(B, S, n_heads))
 
 
 def taw_op_attn_bwd(dtype, B, S, n_heads, head_dim, qkv, o, dO, lse, dqkv, scratch, impl=TAW_IMPL_AUTO, stream=None):

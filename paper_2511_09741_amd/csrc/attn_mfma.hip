@@ -17,6 +17,9 @@
 // The A operands V^T, K^T, dO^T, Q^T are "transposed" tiles: they are read from the row-major LDS
 // tile with ds_read_b64_tr_b16, which returns 4 consecutive rows of one column per lane: exactly
 // the 4-row groups of the accumulator layout.  Nothing is transposed through memory.
+#include <type_traits>
+#include <utility>
+
 #include "dev_common.h"
 #include "taw_internal.h"
 
@@ -90,6 +93,59 @@ __device__ __forceinline__ bf16x8_t frag_tr(const bf16_t* tile, int row0, int t,
   return u.v;
 }
 
+typedef __attribute__((address_space(3))) unsigned char lds_u8_t;
+
+// compile-time loop: f(std::integral_constant<int, 0>{}), ..., f(std::integral_constant<int, N - 1>{})
+template <class F, int... I> __device__ __forceinline__ void static_for_impl(F&& f, std::integer_sequence<int, I...>) {
+  (f(std::integral_constant<int, I>{}), ...);
+}
+template <int N, class F> __device__ __forceinline__ void static_for(F&& f) { static_for_impl(f, std::make_integer_sequence<int, N>{}); }
+#define TAW_CONST(name, c) constexpr int name = decltype(c)::value
+
+// ---- the same two fragment reads with hand-made LDS byte addresses --------------------------------
+// Both swizzled addresses are "per-lane constant XOR small immediate": one register per pattern
+// (plus the stage offset, a multiple of 256 bytes, added per tile) instead of one per fragment.
+//   natural:    (nat ^ (ks << 5)) + 256 * row0            nat = (l&31)*256 + chunk bits of ks = 0
+//   transposed: (tr ^ ((dt << 6) | (rr << 5))) + 256 * (row0 + 16 t + 8 rr)
+struct LaneAddr {
+  unsigned nat, tr;
+  __device__ __forceinline__ void init(int lane) {
+    const int r = lane & 31, hh = lane >> 5;
+    nat = r * 256 + (swz(r, hh) << 4);
+    const int blk = lane >> 4, i = lane & 15, h = blk >> 1;
+    const int rl = 4 * h + (i >> 2), d = 16 * (blk & 1) + 4 * (i & 3);
+    tr = rl * 256 + (swz(rl, d >> 3) << 4) + (d & 7) * 2;
+  }
+};
+// x ^ k.  OPAQUE: computed where it is written; as an opaque instruction the compiler can neither hoist the
+// eight variants of an address out of the loop nor keep them all alive (that costs the registers
+// that decide between two wavefronts per SIMD with or without spills in the dK/dV kernel)
+template <int K, bool OPAQUE> __device__ __forceinline__ unsigned xor_here(unsigned x) {
+  if (K == 0) return x;
+  if (!OPAQUE) return x ^ (unsigned)K;
+  unsigned r;
+  asm volatile("v_xor_b32 %0, %1, %2" : "=v"(r) : "i"(K), "v"(x));
+  return r;
+}
+// nat_t / tr_t: the lane constant plus the LDS byte address of the stage (a multiple of 256);
+// OFF: byte offset of the tile inside the stage plus 256 * row0
+template <int KS, int OFF, bool OPAQUE = false> __device__ __forceinline__ bf16x8_t frag_nat2(unsigned nat_t) {
+  return *reinterpret_cast<const __attribute__((address_space(3))) bf16x8_t*>(xor_here<(KS << 5), OPAQUE>(nat_t) + OFF);
+}
+// both transposing reads of fragment (t, dt) at tile offsets OFF0 and OFF1 (two tiles of one stage share the address)
+template <int T, int DT, int OFF0, int OFF1, bool OPAQUE = false>
+__device__ __forceinline__ void frag_tr2x2(unsigned tr_t, bf16x8_t& f0, bf16x8_t& f1) {
+  union { s16x4_t h2[2]; bf16x8_t v; } u0, u1;
+#pragma unroll
+  for (int rr = 0; rr < 2; ++rr) {
+    const unsigned a = (rr == 0 ? xor_here<(DT << 6), OPAQUE>(tr_t) : xor_here<((DT << 6) | 32), OPAQUE>(tr_t)) + (16 * T + 8 * rr) * 256;
+    u0.h2[rr] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(reinterpret_cast<s16x4_t __attribute__((address_space(3)))*>(a + OFF0));
+    if (OFF1 >= 0) u1.h2[rr] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(reinterpret_cast<s16x4_t __attribute__((address_space(3)))*>(a + OFF1));
+  }
+  f0 = u0.v;
+  if (OFF1 >= 0) f1 = u1.v;
+}
+
 __device__ __forceinline__ bf16x8_t pack8(const f32x16_t& x, int t) {
   bf16x8_t p;
 #pragma unroll
@@ -98,8 +154,6 @@ __device__ __forceinline__ bf16x8_t pack8(const f32x16_t& x, int t) {
 }
 
 // ---- direct global -> LDS tile loads ----------------------------------------------------------------
-typedef __attribute__((address_space(3))) unsigned char lds_u8_t;
-
 // s_waitcnt vmcnt(n) with the other counters left alone (gfx9 encoding: vmcnt[3:0] | expcnt<<4 | lgkmcnt<<8 | vmcnt[5:4]<<14)
 template <int N> __device__ __forceinline__ void wait_vmcnt() {
   __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (15 << 8) | ((N >> 4) << 14));
@@ -160,11 +214,14 @@ __global__ void __launch_bounds__(kThreads8, 1)
 attn_fwd_kernel(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ o, float* __restrict__ lse, int B, int S, int nh, float scale) {
   constexpr int BQ = 256, WQ = 32, BKV = 64, NS = 4;
   constexpr int kStage = 2 * kTileBytes;   // K tile | V tile
-  extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
-  const unsigned lds0 = (unsigned)(size_t)(const lds_u8_t*)lds_raw;
+  extern __shared__ __attribute__((aligned(256))) unsigned char lds_raw[];
+  const lds_u8_t* L = (const lds_u8_t*)lds_raw;
+  const unsigned lds0 = (unsigned)(size_t)L;
 
   const int tid = threadIdx.x, lane = tid & 63, hh = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  LaneAddr la;
+  la.init(lane);
   const int nqt = (S + BQ - 1) / BQ;
   const int bh = blockIdx.x % (B * nh);
   const int qt = nqt - 1 - blockIdx.x / (B * nh);      // longest rows first
@@ -183,7 +240,7 @@ attn_fwd_kernel(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ o, float* _
     tile_dma(kbase, ldb, t * BKV, S, st, lane, wave);
     tile_dma(vbase, ldb, t * BKV, S, st + kTileBytes, lane, wave);
   };
-  for (int t = 0; t < NS - 1 && t < nkv; ++t) issue(t);
+  for (int t = 0; t < NS - 2 && t < nkv; ++t) issue(t);
 
   // Q as B operands, straight from global memory
   bf16x8_t qf[8];
@@ -201,26 +258,55 @@ attn_fwd_kernel(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ o, float* _
     for (int r = 0; r < 16; ++r) oacc[dt][r] = 0.f;
   const int qidx = q0w + (lane & 31);
 
+  // The two wavefronts of a SIMD (w and w + 4) run the three phases of a tile in different orders, so
+  // that one's softmax arithmetic meets the other's MFMAs instead of both doing the same thing after
+  // every barrier: wavefronts 0..3 do S = K Q^T, softmax, O += V^T P within the tile's period; the
+  // late ones 4..7 start a period with the O += V^T P of the previous tile (its P waits in registers,
+  // its V stays in the ring one period longer, which is why tiles are issued two ahead, not three).
+  const bool late = wave >= kWaves8 / 2;
+  bf16x8_t pf[2][2];
+  bool pend = false;
+  unsigned pend_tr = 0;
+  auto pv = [&](unsigned tr_t) {
+    static_for<2>([&](auto kb_c) {
+      TAW_CONST(kb, kb_c);
+      static_for<2>([&](auto t_c) {
+        TAW_CONST(t, t_c);
+        static_for<4>([&](auto dt_c) {
+          TAW_CONST(dt, dt_c);
+          bf16x8_t vfr, unused;
+          frag_tr2x2<t, dt, kTileBytes + kb * 8192, -1>(tr_t, vfr, unused);
+          oacc[dt] = mfma(vfr, pf[kb][t], oacc[dt]);
+        });
+      });
+    });
+  };
+
   for (int j = 0; j < nkv; ++j) {
     // tile j has landed (each wavefront waits for its own pieces, the barrier collects them); the
-    // barrier also says every wavefront is done with tile j-1, whose stage tile j+3 goes into
-    const int ahead = nkv - 1 - j;
-    if (ahead >= 2) wait_vmcnt<8>(); else if (ahead == 1) wait_vmcnt<4>(); else wait_vmcnt<0>();
+    // barrier also says every wavefront is done with tile j-2, whose stage tile j+2 goes into
+    if (j + 1 < nkv) wait_vmcnt<4>(); else wait_vmcnt<0>();
     stage_barrier();
-    if (j + NS - 1 < nkv) issue(j + NS - 1);
+    if (j + NS - 2 < nkv) issue(j + NS - 2);
+    if (pend) {                                        // late wavefronts: the previous tile's O += V^T P
+      pv(pend_tr);
+      pend = false;
+    }
     const int kv0 = j * BKV;
     if (kv0 > q0w + WQ - 1) continue;                  // no key of the tile is visible to this wavefront
-    const bf16_t* sk = reinterpret_cast<const bf16_t*>(lds_raw + (j & (NS - 1)) * kStage);
-    const bf16_t* sv = sk + 64 * D;
+    const unsigned so = lds0 + (j & (NS - 1)) * kStage;
+    const unsigned nat_t = la.nat + so, tr_t = la.tr + so;
 
     f32x16_t s[2];
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb) {
+    static_for<2>([&](auto kb_c) {
+      TAW_CONST(kb, kb_c);
 #pragma unroll
       for (int r = 0; r < 16; ++r) s[kb][r] = 0.f;
-#pragma unroll
-      for (int ks = 0; ks < 8; ++ks) s[kb] = mfma(frag_nat(sk, kb * 32, ks, lane), qf[ks], s[kb]);
-    }
+      static_for<8>([&](auto ks_c) {
+        TAW_CONST(ks, ks_c);
+        s[kb] = mfma(frag_nat2<ks, kb * 8192>(nat_t), qf[ks], s[kb]);
+      });
+    });
     if (kv0 + BKV - 1 > q0w) {                         // tile crosses the diagonal (or the end of the sequence)
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb)
@@ -257,12 +343,15 @@ attn_fwd_kernel(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ o, float* _
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-      for (int t = 0; t < 2; ++t) {
-        const bf16x8_t pf = pack8(s[kb], t);
-#pragma unroll
-        for (int dt = 0; dt < 4; ++dt) oacc[dt] = mfma(frag_tr(sv, kb * 32, t, dt * 32, lane), pf, oacc[dt]);
-      }
+      for (int t = 0; t < 2; ++t) pf[kb][t] = pack8(s[kb], t);
+    if (late) {
+      pend = true;
+      pend_tr = tr_t;
+    } else {
+      pv(tr_t);
+    }
   }
+  if (pend) pv(pend_tr);
   __syncthreads();          // every wavefront is done with the ring: it becomes the output staging area
 
   // ---- epilogue: O^T accumulators -> [q][136] bf16 staging in LDS -> coalesced rows of o
@@ -322,6 +411,40 @@ __device__ __forceinline__ void store_rows_T(const f32x16_t (&acc)[4], float mul
   __builtin_amdgcn_wave_barrier();
 }
 
+// =============================================================================== backward: row statistics
+// prep [2][B*nh][Sp] fp32, Sp = S rounded up to 64:  prep[0] = lse * log2(e) (what the exp2-domain
+// recomputation subtracts), +inf for rows S..Sp-1 so that their probabilities come out as exactly 0;
+// prep[1] = D[t] = dO[t] . o[t], 0 for the padding rows.  16 lanes share one (row, head): a wavefront
+// reads 1 KiB of contiguous o / dO.
+__global__ void __launch_bounds__(256) attn_bwd_prep_kernel(const bf16_t* __restrict__ o, const bf16_t* __restrict__ dO,
+                                                            const float* __restrict__ lse, float* __restrict__ prep,
+                                                            int B, int S, int Sp, int nh) {
+  const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  const int part = (int)(gid & 15);
+  const int64_t pair = gid >> 4;                       // (b, s in [0, Sp), h), h fastest
+  const int64_t npairs = (int64_t)B * Sp * nh;
+  if (pair >= npairs) return;                          // whole 16-lane groups leave together
+  const int h = (int)(pair % nh);
+  const int64_t bs = pair / nh;
+  const int sidx = (int)(bs % Sp), b = (int)(bs / Sp);
+  float dot = 0.f, l2 = INFINITY;
+  if (sidx < S) {
+    const int64_t off = ((int64_t)b * S + sidx) * ((int64_t)nh * D) + (int64_t)h * D + part * 8;
+    const bf16x8_t a = *reinterpret_cast<const bf16x8_t*>(o + off);
+    const bf16x8_t g = *reinterpret_cast<const bf16x8_t*>(dO + off);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) dot += (float)a[j] * (float)g[j];
+    l2 = lse[((int64_t)b * nh + h) * S + sidx] * kLog2e;
+  }
+#pragma unroll
+  for (int m = 8; m > 0; m >>= 1) dot += __shfl_xor(dot, m, 64);
+  if (part == 0) {
+    const int64_t at = ((int64_t)b * nh + h) * Sp + sidx;
+    prep[at] = l2;
+    prep[(int64_t)B * nh * Sp + at] = dot;
+  }
+}
+
 // =============================================================================== backward: dK, dV
 // Workgroup: 8 wavefronts, one (batch, head, 256 keys); wavefront w owns keys 32w..32w+31 and keeps
 // their K and V rows in registers as B operands.  Query rows stream through a 4-stage LDS ring in
@@ -330,15 +453,18 @@ __device__ __forceinline__ void store_rows_T(const f32x16_t (&acc)[4], float mul
 //   S = Q K^T;  P = exp(S/sqrt(d) - lse);  dP = dO V^T;  dS = P (dP - D)
 //   dV^T += dO^T P;   dK^T += Q^T dS  (scaled by 1/sqrt(d) at the end)
 __global__ void __launch_bounds__(kThreads8, 1)
-attn_bwd_dkv_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dO, const float* __restrict__ lse,
-                    const float* __restrict__ Dsum, bf16_t* __restrict__ dqkv, int B, int S, int nh, float scale) {
+attn_bwd_dkv_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dO, const float* __restrict__ lse2,
+                    const float* __restrict__ Dsum, bf16_t* __restrict__ dqkv, int B, int S, int Sp, int nh, float scale) {
   constexpr int BKVW = 256, BQ = 64, NS = 4;
   constexpr int kStage = 2 * kTileBytes + 2 * BQ * 4;   // Q tile | dO tile | lse[64] | D[64]
-  extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
-  const unsigned lds0 = (unsigned)(size_t)(const lds_u8_t*)lds_raw;
+  extern __shared__ __attribute__((aligned(256))) unsigned char lds_raw[];
+  const lds_u8_t* L = (const lds_u8_t*)lds_raw;
+  const unsigned lds0 = (unsigned)(size_t)L;
 
   const int tid = threadIdx.x, lane = tid & 63, hh = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  LaneAddr la;
+  la.init(lane);
   const int bh = blockIdx.x % (B * nh);
   const int kt = blockIdx.x / (B * nh);                 // early key tiles see the most queries: they go first
   const int b = bh / nh, h = bh % nh;
@@ -347,7 +473,7 @@ attn_bwd_dkv_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ d
   const bf16_t* kbase = qbase + H;
   const bf16_t* vbase = qbase + 2 * H;
   const uint64_t qb64 = (uint64_t)qbase, do64 = (uint64_t)(dO + (int64_t)b * S * H + (int64_t)h * D);
-  const uint64_t l64 = (uint64_t)(lse + ((int64_t)b * nh + h) * S), d64 = (uint64_t)(Dsum + ((int64_t)b * nh + h) * S);
+  const uint64_t l64 = (uint64_t)(lse2 + ((int64_t)b * nh + h) * Sp), d64 = (uint64_t)(Dsum + ((int64_t)b * nh + h) * Sp);
   const unsigned ldb = (unsigned)(ld * 2), ldob = (unsigned)(H * 2);
   const int kv0 = kt * BKVW, kv0w = kv0 + wave * 32;
   const float c = scale * kLog2e;
@@ -359,11 +485,8 @@ attn_bwd_dkv_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ d
     const int row0 = (jb + t) * BQ;
     tile_dma(qb64, ldb, row0, S, st, lane, wave);
     tile_dma(do64, ldob, row0, S, st + kTileBytes, lane, wave);
-    if (wave < 2) {                                     // wavefront 0: the block's lse; wavefront 1: its D
-      int row = row0 + lane;
-      row = row < S ? row : S - 1;
-      lds_dma4(wave == 0 ? l64 : d64, (unsigned)row * 4u, st + 2 * kTileBytes + wave * (BQ * 4));
-    }
+    if (wave < 2)                                       // wavefront 0: the block's scaled lse; wavefront 1: its D (both padded to Sp rows)
+      lds_dma4(wave == 0 ? l64 : d64, (unsigned)(row0 + lane) * 4u, st + 2 * kTileBytes + wave * (BQ * 4));
   };
   for (int t = 0; t < NS - 1 && t < nblk; ++t) issue(t);
 
@@ -392,51 +515,73 @@ attn_bwd_dkv_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ d
     if (t + NS - 1 < nblk) issue(t + NS - 1);
     const int qb0 = (jb + t) * BQ;
     if (qb0 + BQ - 1 < kv0w) continue;                   // no query of the block sees this wavefront's keys
-    const unsigned char* stg = lds_raw + (t & (NS - 1)) * kStage;
-    const bf16_t* sq = reinterpret_cast<const bf16_t*>(stg);
-    const bf16_t* sdo = sq + 64 * D;
-    const float* sl = reinterpret_cast<const float*>(stg + 2 * kTileBytes);
-    const float* sd = sl + BQ;
-#pragma unroll
-    for (int qb = 0; qb < 2; ++qb) {
+    const unsigned so = lds0 + (t & (NS - 1)) * kStage;
+    const unsigned nat_t = la.nat + so, tr_t = la.tr + so;
+    const unsigned sl = so + 2 * kTileBytes + 16 * hh;     // lse, then D, of the block's rows 4 hh ..
+    static_for<2>([&](auto qb_c) {
+      TAW_CONST(qb, qb_c);
       const int qrow0 = qb0 + qb * 32;
-      if (qrow0 + 31 < kv0w) continue;                   // wavefront-uniform
-      f32x16_t sacc, pacc;
+      if (qrow0 + 31 < kv0w) return;                     // wavefront-uniform
+      typedef const __attribute__((address_space(3))) f32x4_t* lds_f4_t;
+      // S and P first; P is kept only as the bf16 operand of the dV product (dS below is formed from
+      // those rounded values too), so that the second accumulator does not have to coexist with the first
+      bf16x8_t pb[2], dsb[2];
+      {
+        f32x16_t sacc;
 #pragma unroll
-      for (int r = 0; r < 16; ++r) { sacc[r] = 0.f; pacc[r] = 0.f; }
+        for (int r = 0; r < 16; ++r) sacc[r] = 0.f;
+        static_for<8>([&](auto ks_c) {
+          TAW_CONST(ks, ks_c);
+          sacc = mfma(frag_nat2<ks, qb * 8192, true>(nat_t), kf[ks], sacc);
+        });
+        if (qrow0 < kv0w + 31) {                         // block crosses the diagonal (wavefront-uniform): invisible pairs get score -inf
+          asm volatile("" ::: "memory");                 // keeps this a branch: most blocks skip the compares
 #pragma unroll
-      for (int ks = 0; ks < 8; ++ks) {
-        sacc = mfma(frag_nat(sq, qb * 32, ks, lane), kf[ks], sacc);
-        pacc = mfma(frag_nat(sdo, qb * 32, ks, lane), vf[ks], pacc);
-      }
-      const bool need_mask = (qrow0 < kv0w + 31) || (qrow0 + 31 >= S);
-#pragma unroll
-      for (int r4 = 0; r4 < 4; ++r4) {
-        const int rbase = qb * 32 + 8 * r4 + 4 * hh;
-        const f32x4_t l4 = *reinterpret_cast<const f32x4_t*>(sl + rbase);
-        const f32x4_t d4 = *reinterpret_cast<const f32x4_t*>(sd + rbase);
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const int r = 4 * r4 + e;
-          float p = fast_exp2(__builtin_fmaf(sacc[r], c, -l4[e] * kLog2e));
-          if (need_mask) {
-            const int qi = qb0 + rbase + e;
-            p = (kvi > qi || qi >= S) ? 0.f : p;
+          for (int r = 0; r < 16; ++r) {
+            const int qi = qrow0 + 8 * (r >> 2) + 4 * hh + (r & 3);
+            sacc[r] = kvi > qi ? -INFINITY : sacc[r];
           }
-          sacc[r] = p;
-          pacc[r] = p * (pacc[r] - d4[e]);
         }
-      }
 #pragma unroll
-      for (int tt = 0; tt < 2; ++tt) {
-        const bf16x8_t pb = pack8(sacc, tt), dsb = pack8(pacc, tt);
+        for (int r4 = 0; r4 < 4; ++r4) {
+          const f32x4_t l4 = *reinterpret_cast<lds_f4_t>(sl + (qb * 32 + 8 * r4) * 4);     // +inf for rows beyond S: p = 0
 #pragma unroll
-        for (int dt = 0; dt < 4; ++dt) {
-          dv[dt] = mfma(frag_tr(sdo, qb * 32, tt, dt * 32, lane), pb, dv[dt]);
-          dk[dt] = mfma(frag_tr(sq, qb * 32, tt, dt * 32, lane), dsb, dk[dt]);
+          for (int e = 0; e < 4; ++e) sacc[4 * r4 + e] = fast_exp2(__builtin_fmaf(sacc[4 * r4 + e], c, -l4[e]));
         }
+#pragma unroll
+        for (int tt = 0; tt < 2; ++tt) pb[tt] = pack8(sacc, tt);
       }
-    }
+      {
+        f32x16_t pacc;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) pacc[r] = 0.f;
+        static_for<8>([&](auto ks_c) {
+          TAW_CONST(ks, ks_c);
+          pacc = mfma(frag_nat2<ks, kTileBytes + qb * 8192, true>(nat_t), vf[ks], pacc);
+        });
+#pragma unroll
+        for (int r4 = 0; r4 < 4; ++r4) {
+          const f32x4_t d4 = *reinterpret_cast<lds_f4_t>(sl + (BQ + qb * 32 + 8 * r4) * 4);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const int r = 4 * r4 + e;
+            pacc[r] = (float)pb[r >> 3][r & 7] * (pacc[r] - d4[e]);
+          }
+        }
+#pragma unroll
+        for (int tt = 0; tt < 2; ++tt) dsb[tt] = pack8(pacc, tt);
+      }
+      static_for<4>([&](auto dt_c) {
+        TAW_CONST(dt, dt_c);
+        static_for<2>([&](auto tt_c) {
+          TAW_CONST(tt, tt_c);
+          bf16x8_t fq, fdo;
+          frag_tr2x2<tt, dt, qb * 8192, kTileBytes + qb * 8192, true>(tr_t, fq, fdo);
+          dv[dt] = mfma(fdo, pb[tt], dv[dt]);
+          dk[dt] = mfma(fq, dsb[tt], dk[dt]);
+        });
+      });
+    });
   }
   __syncthreads();          // the ring becomes the output staging area
 
@@ -453,15 +598,18 @@ attn_bwd_dkv_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ d
 //   S^T = K Q^T;  P^T = exp(S^T/sqrt(d) - lse);  dP^T = V dO^T;  dS^T = P^T (dP^T - D);
 //   dQ^T += K^T dS^T  (scaled by 1/sqrt(d) at the end)
 __global__ void __launch_bounds__(kThreads8, 1)
-attn_bwd_dq_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dO, const float* __restrict__ lse,
-                   const float* __restrict__ Dsum, bf16_t* __restrict__ dqkv, int B, int S, int nh, float scale) {
+attn_bwd_dq_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dO, const float* __restrict__ lse2,
+                   const float* __restrict__ Dsum, bf16_t* __restrict__ dqkv, int B, int S, int Sp, int nh, float scale) {
   constexpr int BQ = 256, WQ = 32, BKV = 64, NS = 4;
   constexpr int kStage = 2 * kTileBytes;   // K tile | V tile
-  extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
-  const unsigned lds0 = (unsigned)(size_t)(const lds_u8_t*)lds_raw;
+  extern __shared__ __attribute__((aligned(256))) unsigned char lds_raw[];
+  const lds_u8_t* L = (const lds_u8_t*)lds_raw;
+  const unsigned lds0 = (unsigned)(size_t)L;
 
   const int tid = threadIdx.x, lane = tid & 63, hh = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  LaneAddr la;
+  la.init(lane);
   const int nqt = (S + BQ - 1) / BQ;
   const int bh = blockIdx.x % (B * nh);
   const int qt = nqt - 1 - blockIdx.x / (B * nh);
@@ -494,8 +642,8 @@ attn_bwd_dq_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dO
       qf[ks] = *reinterpret_cast<const bf16x8_t*>(qbase + (int64_t)row * ld + 16 * ks + 8 * hh);
       dof[ks] = *reinterpret_cast<const bf16x8_t*>(dobase + (int64_t)row * H + 16 * ks + 8 * hh);
     }
-    l2 = lse[((int64_t)b * nh + h) * S + row] * kLog2e;
-    dsum = Dsum[((int64_t)b * nh + h) * S + row];
+    l2 = lse2[((int64_t)b * nh + h) * Sp + row];
+    dsum = Dsum[((int64_t)b * nh + h) * Sp + row];
 #pragma unroll
     for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
@@ -510,35 +658,43 @@ attn_bwd_dq_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dO
     if (j + NS - 1 < nkv) issue(j + NS - 1);
     const int kv0 = j * BKV;
     if (kv0 > q0w + WQ - 1) continue;
-    const bf16_t* sk = reinterpret_cast<const bf16_t*>(lds_raw + (j & (NS - 1)) * kStage);
-    const bf16_t* sv = sk + 64 * D;
+    const unsigned so = lds0 + (j & (NS - 1)) * kStage;
+    const unsigned nat_t = la.nat + so, tr_t = la.tr + so;
     const bool need_mask = kv0 + BKV - 1 > q0w;
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb) {
+    static_for<2>([&](auto kb_c) {
+      TAW_CONST(kb, kb_c);
       f32x16_t sacc, pacc;
 #pragma unroll
       for (int r = 0; r < 16; ++r) { sacc[r] = 0.f; pacc[r] = 0.f; }
+      static_for<8>([&](auto ks_c) {
+        TAW_CONST(ks, ks_c);
+        sacc = mfma(frag_nat2<ks, kb * 8192>(nat_t), qf[ks], sacc);
+        pacc = mfma(frag_nat2<ks, kTileBytes + kb * 8192>(nat_t), dof[ks], pacc);
+      });
+      if (need_mask) {                                   // wavefront-uniform
+        asm volatile("" ::: "memory");                   // keeps this a branch: most tiles skip the compares
 #pragma unroll
-      for (int ks = 0; ks < 8; ++ks) {
-        sacc = mfma(frag_nat(sk, kb * 32, ks, lane), qf[ks], sacc);
-        pacc = mfma(frag_nat(sv, kb * 32, ks, lane), dof[ks], pacc);
+        for (int r = 0; r < 16; ++r) {
+          const int kv = kv0 + kb * 32 + 8 * (r >> 2) + 4 * hh + (r & 3);
+          sacc[r] = kv > qidx ? -INFINITY : sacc[r];
+        }
       }
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        float p = fast_exp2(__builtin_fmaf(sacc[r], c, -l2));
-        if (need_mask) {
-          const int kv = kv0 + kb * 32 + 8 * (r >> 2) + 4 * hh + (r & 3);
-          p = kv > qidx ? 0.f : p;
-        }
+        const float p = fast_exp2(__builtin_fmaf(sacc[r], c, -l2));
         pacc[r] = p * (pacc[r] - dsum);
       }
-#pragma unroll
-      for (int t = 0; t < 2; ++t) {
+      static_for<2>([&](auto t_c) {
+        TAW_CONST(t, t_c);
         const bf16x8_t dsb = pack8(pacc, t);
-#pragma unroll
-        for (int dt = 0; dt < 4; ++dt) dq[dt] = mfma(frag_tr(sk, kb * 32, t, dt * 32, lane), dsb, dq[dt]);
-      }
-    }
+        static_for<4>([&](auto dt_c) {
+          TAW_CONST(dt, dt_c);
+          bf16x8_t fk, unused;
+          frag_tr2x2<t, dt, kb * 8192, -1>(tr_t, fk, unused);
+          dq[dt] = mfma(fk, dsb, dq[dt]);
+        });
+      });
+    });
   }
   __syncthreads();          // the ring becomes the output staging area
 
@@ -569,16 +725,29 @@ int launch_attn_fwd_mfma(int B, int S, int nh, const void* qkv, void* o, float* 
   return launch_fwd(B, S, nh, qkv, o, lse, st);
 }
 
-int launch_attn_bwd_mfma(int B, int S, int nh, const void* qkv, const void* dO, const float* lse, const float* Dv, void* dqkv, hipStream_t st) {
+size_t attn_bwd_mfma_scratch_floats(int B, int S, int nh) { return 2 * (size_t)B * nh * ((S + 63) / 64 * 64); }
+
+int launch_attn_bwd_mfma(int B, int S, int nh, const void* qkv, const void* o, const void* dO, const float* lse, float* prep,
+                         void* dqkv, hipStream_t st) {
   const float scale = 1.0f / sqrtf((float)D);
+  const int Sp = (S + 63) / 64 * 64;
+  const float* lse2 = prep;
+  const float* Dv = prep + (size_t)B * nh * Sp;
+  {
+    const int64_t threads = (int64_t)B * Sp * nh * 16;
+    hipLaunchKernelGGL(attn_bwd_prep_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st, (const bf16_t*)o, (const bf16_t*)dO, lse, prep,
+                       B, S, Sp, nh);
+    int rc = (int)hipGetLastError();
+    if (rc) return rc;
+  }
   {
     constexpr size_t lds = 4 * (2 * kTileBytes + 2 * 64 * sizeof(float));
     static_assert(lds >= 8 * 32 * 136 * sizeof(bf16_t), "staging area");
     hipError_t e = hipFuncSetAttribute((const void*)attn_bwd_dkv_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return (int)e;
     const int nkt = (S + 255) / 256;
-    hipLaunchKernelGGL(attn_bwd_dkv_kernel, dim3((unsigned)(nkt * B * nh)), dim3(kThreads8), lds, st, (const bf16_t*)qkv, (const bf16_t*)dO, lse, Dv,
-                       (bf16_t*)dqkv, B, S, nh, scale);
+    hipLaunchKernelGGL(attn_bwd_dkv_kernel, dim3((unsigned)(nkt * B * nh)), dim3(kThreads8), lds, st, (const bf16_t*)qkv, (const bf16_t*)dO, lse2, Dv,
+                       (bf16_t*)dqkv, B, S, Sp, nh, scale);
     int rc = (int)hipGetLastError();
     if (rc) return rc;
   }
@@ -587,8 +756,8 @@ int launch_attn_bwd_mfma(int B, int S, int nh, const void* qkv, const void* dO, 
     hipError_t e = hipFuncSetAttribute((const void*)attn_bwd_dq_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return (int)e;
     const int nqt = (S + 255) / 256;
-    hipLaunchKernelGGL(attn_bwd_dq_kernel, dim3((unsigned)(nqt * B * nh)), dim3(kThreads8), lds, st, (const bf16_t*)qkv, (const bf16_t*)dO, lse, Dv,
-                       (bf16_t*)dqkv, B, S, nh, scale);
+    hipLaunchKernelGGL(attn_bwd_dq_kernel, dim3((unsigned)(nqt * B * nh)), dim3(kThreads8), lds, st, (const bf16_t*)qkv, (const bf16_t*)dO, lse2, Dv,
+                       (bf16_t*)dqkv, B, S, Sp, nh, scale);
     return (int)hipGetLastError();
   }
 }

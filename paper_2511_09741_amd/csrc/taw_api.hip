@@ -131,7 +131,7 @@ static Work carve_work(const taw_layer_desc* d, void* base) {
   Carve c(base); Work w;
   w.da = c.take(T * I * e); w.dgu = c.take(T * 2 * I * e); w.dhn = c.take(T * H * e); w.dh = c.take(T * H * e);
   w.dO = c.take(T * H * e); w.dqkv = c.take(T * 3 * H * e); w.dxn = c.take(T * H * e);
-  w.D = (float*)c.take((size_t)d->B * d->n_heads * d->S * 4);
+  w.D = (float*)c.take(attn_bwd_mfma_scratch_floats(d->B, d->S, d->n_heads) * 4);   // covers the generic kernel's B*nh*S too
   w.partials = (float*)c.take((size_t)rmsnorm_bwd_partial_rows() * H * 4);
   w.bytes = c.off;
   return w;
@@ -247,9 +247,12 @@ extern "C" int taw_layer_bwd(const taw_layer_desc* desc, const void* W_chunk, co
   TAW_LAUNCH(gemm(p, dt, GEMM_NN, T, H, H, w.dh, H, at(W_chunk, L.w_o, dt), H, w.dO, H, dt, 0, nullptr, 0, st), "gemm do");
   TAW_LAUNCH(gemm(p, dt, GEMM_TN, H, H, T, w.dh, H, c.o, H, G_shard + L.w_o, H, DT_F32, acc, nullptr, 0, st), "gemm G.w_o");
   // attention backward
-  TAW_LAUNCH(launch_attn_rowdot(dt, desc->B, desc->S, desc->n_heads, desc->head_dim, c.o, H, w.dO, H, w.D, st), "attention row dot");
-  if (p.mfma_attn) TAW_LAUNCH(launch_attn_bwd_mfma(desc->B, desc->S, desc->n_heads, c.qkv, w.dO, c.lse, w.D, w.dqkv, st), "attention bwd (mfma)");
-  else TAW_LAUNCH(launch_attn_bwd_generic(dt, desc->B, desc->S, desc->n_heads, desc->head_dim, c.qkv, w.dO, c.lse, w.D, w.dqkv, st), "attention bwd (generic)");
+  if (p.mfma_attn) {
+    TAW_LAUNCH(launch_attn_bwd_mfma(desc->B, desc->S, desc->n_heads, c.qkv, c.o, w.dO, c.lse, w.D, w.dqkv, st), "attention bwd (mfma)");
+  } else {
+    TAW_LAUNCH(launch_attn_rowdot(dt, desc->B, desc->S, desc->n_heads, desc->head_dim, c.o, H, w.dO, H, w.D, st), "attention row dot");
+    TAW_LAUNCH(launch_attn_bwd_generic(dt, desc->B, desc->S, desc->n_heads, desc->head_dim, c.qkv, w.dO, c.lse, w.D, w.dqkv, st), "attention bwd (generic)");
+  }
   // rotary backward on dq, dk
   TAW_LAUNCH(launch_rope(dt, desc->B, desc->S, (int)(2 * H), desc->head_dim, w.dqkv, 3 * H, rope_table, 1, st), "rope bwd");
   // qkv = xn Wqkv^T :  dxn = dqkv Wqkv ;  G.Wqkv (+)= dqkv^T xn
@@ -411,6 +414,11 @@ extern "C" int taw_op_attn_fwd(int32_t dtype, int32_t B, int32_t S, int32_t n_he
   return TAW_OK;
 }
 
+extern "C" size_t taw_op_attn_bwd_scratch_floats(int32_t B, int32_t S, int32_t n_heads) {
+  if (B <= 0 || S <= 0 || n_heads <= 0) return 0;
+  return attn_bwd_mfma_scratch_floats(B, S, n_heads);
+}
+
 extern "C" int taw_op_attn_bwd(int32_t dtype, int32_t B, int32_t S, int32_t n_heads, int32_t head_dim, const void* qkv, const void* o,
                                const void* dO, const float* lse, void* dqkv, float* scratch, int32_t impl, void* stream) {
   bool mf;
@@ -421,8 +429,11 @@ extern "C" int taw_op_attn_bwd(int32_t dtype, int32_t B, int32_t S, int32_t n_he
   TAW_REQUIRE_ALIGNED(scratch);
   const hipStream_t st = (hipStream_t)stream;
   const int64_t H = (int64_t)n_heads * head_dim;
-  TAW_LAUNCH(launch_attn_rowdot(dtype, B, S, n_heads, head_dim, o, H, dO, H, scratch, st), "attention row dot");
-  if (mf) TAW_LAUNCH(launch_attn_bwd_mfma(B, S, n_heads, qkv, dO, lse, scratch, dqkv, st), "attention bwd (mfma)");
-  else TAW_LAUNCH(launch_attn_bwd_generic(dtype, B, S, n_heads, head_dim, qkv, dO, lse, scratch, dqkv, st), "attention bwd (generic)");
+  if (mf) {
+    TAW_LAUNCH(launch_attn_bwd_mfma(B, S, n_heads, qkv, o, dO, lse, scratch, dqkv, st), "attention bwd (mfma)");
+  } else {
+    TAW_LAUNCH(launch_attn_rowdot(dtype, B, S, n_heads, head_dim, o, H, dO, H, scratch, st), "attention row dot");
+    TAW_LAUNCH(launch_attn_bwd_generic(dtype, B, S, n_heads, head_dim, qkv, dO, lse, scratch, dqkv, st), "attention bwd (generic)");
+  }
   return TAW_OK;
 }

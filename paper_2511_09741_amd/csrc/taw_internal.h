@@ -60,7 +60,10 @@ int launch_gemm_mfma(int mode, int64_t M, int64_t N, int64_t K, const void* A, i
 // bf16, head_dim 128, and S * 3 * n_heads * head_dim * 2 bytes below 4 GiB (32-bit row offsets inside one batch element)
 bool attn_mfma_supported(int dtype, int S, int nh, int d);
 int launch_attn_fwd_mfma(int B, int S, int nh, const void* qkv, void* o, float* lse, hipStream_t st);
-int launch_attn_bwd_mfma(int B, int S, int nh, const void* qkv, const void* dO, const float* lse,
-                         const float* D, void* dqkv, hipStream_t st);
+// fp32 scratch of the MFMA backward: scaled lse and D, each padded to a multiple of 64 rows per (batch, head)
+size_t attn_bwd_mfma_scratch_floats(int B, int S, int nh);
+// computes its own row statistics (scratch) from o, dO and lse
+int launch_attn_bwd_mfma(int B, int S, int nh, const void* qkv, const void* o, const void* dO, const float* lse,
+                         float* scratch, void* dqkv, hipStream_t st);
 
 }  // namespace taw

@@ -186,7 +186,7 @@ def _attn_case(taw, dtype, B, S, nh, d, impl, seed=0, scale=1.0):
     dref = np.concatenate([dq.reshape(B * S, H), dk.reshape(B * S, H), dv.reshape(B * S, H)], axis=1)
     lse_ref32 = torch.from_numpy(lref.astype(np.float32).reshape(-1)).cuda()
     dqkv = U.empty_dev((B * S, 3 * H), dtype)
-    scratch = torch.empty(B * nh * S, dtype=torch.float32, device="cuda")
+    scratch = torch.empty(taw.taw_op_attn_bwd_scratch_floats(B, S, nh), dtype=torch.float32, device="cuda")
     taw.taw_op_attn_bwd(dtype, B, S, nh, d, qkvd, U.to_dev(o_st, dtype), U.to_dev(dO, dtype), lse_ref32, dqkv, scratch, impl)
     got = U.from_dev(dqkv)
     # at S = 1 the exact dq and dk are identically zero: measure them on the scale of dv
