@@ -268,6 +268,7 @@ attn_fwd_kernel(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ o, float* _
   bool pend = false;
   unsigned pend_tr = 0;
   auto pv = [&](unsigned tr_t) {
+    __builtin_amdgcn_s_setprio(1);
     static_for<2>([&](auto kb_c) {
       TAW_CONST(kb, kb_c);
       static_for<2>([&](auto t_c) {
@@ -280,8 +281,12 @@ attn_fwd_kernel(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ o, float* _
         });
       });
     });
+    __builtin_amdgcn_s_setprio(0);
   };
 
+  // The register-resident operands loaded above have arrived: said here, once, so that the compiler
+  // does not wait for them (and with them for every tile load in flight) at their first use inside the loop.
+  wait_vmcnt<0>();
   for (int j = 0; j < nkv; ++j) {
     // tile j has landed (each wavefront waits for its own pieces, the barrier collects them); the
     // barrier also says every wavefront is done with tile j-2, whose stage tile j+2 goes into
@@ -298,6 +303,7 @@ attn_fwd_kernel(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ o, float* _
     const unsigned nat_t = la.nat + so, tr_t = la.tr + so;
 
     f32x16_t s[2];
+    __builtin_amdgcn_s_setprio(1);
     static_for<2>([&](auto kb_c) {
       TAW_CONST(kb, kb_c);
 #pragma unroll
@@ -307,6 +313,7 @@ attn_fwd_kernel(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ o, float* _
         s[kb] = mfma(frag_nat2<ks, kb * 8192>(nat_t), qf[ks], s[kb]);
       });
     });
+    __builtin_amdgcn_s_setprio(0);
     if (kv0 + BKV - 1 > q0w) {                         // tile crosses the diagonal (or the end of the sequence)
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb)
@@ -507,6 +514,9 @@ attn_bwd_dkv_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ d
     for (int r = 0; r < 16; ++r) { dk[dt][r] = 0.f; dv[dt][r] = 0.f; }
   const int kvi = kv0w + (lane & 31);
 
+  // The register-resident operands loaded above have arrived: said here, once, so that the compiler
+  // does not wait for them (and with them for every tile load in flight) at their first use inside the loop.
+  wait_vmcnt<0>();
   for (int t = 0; t < nblk; ++t) {
     const int ahead = nblk - 1 - t;
     if (wave < 2) { if (ahead >= 2) wait_vmcnt<10>(); else if (ahead == 1) wait_vmcnt<5>(); else wait_vmcnt<0>(); }
@@ -651,6 +661,9 @@ attn_bwd_dq_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dO
   }
   const int qidx = q0w + (lane & 31);
 
+  // The register-resident operands loaded above have arrived: said here, once, so that the compiler
+  // does not wait for them (and with them for every tile load in flight) at their first use inside the loop.
+  wait_vmcnt<0>();
   for (int j = 0; j < nkv; ++j) {
     const int ahead = nkv - 1 - j;
     if (ahead >= 2) wait_vmcnt<8>(); else if (ahead == 1) wait_vmcnt<4>(); else wait_vmcnt<0>();
