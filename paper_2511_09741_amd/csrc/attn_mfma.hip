@@ -540,10 +540,12 @@ attn_bwd_dkv_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ d
         f32x16_t sacc;
 #pragma unroll
         for (int r = 0; r < 16; ++r) sacc[r] = 0.f;
+        __builtin_amdgcn_s_setprio(1);
         static_for<8>([&](auto ks_c) {
           TAW_CONST(ks, ks_c);
           sacc = mfma(frag_nat2<ks, qb * 8192, true>(nat_t), kf[ks], sacc);
         });
+        __builtin_amdgcn_s_setprio(0);
         if (qrow0 < kv0w + 31) {                         // block crosses the diagonal (wavefront-uniform): invisible pairs get score -inf
           asm volatile("" ::: "memory");                 // keeps this a branch: most blocks skip the compares
 #pragma unroll
@@ -565,10 +567,12 @@ attn_bwd_dkv_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ d
         f32x16_t pacc;
 #pragma unroll
         for (int r = 0; r < 16; ++r) pacc[r] = 0.f;
+        __builtin_amdgcn_s_setprio(1);
         static_for<8>([&](auto ks_c) {
           TAW_CONST(ks, ks_c);
           pacc = mfma(frag_nat2<ks, kTileBytes + qb * 8192, true>(nat_t), vf[ks], pacc);
         });
+        __builtin_amdgcn_s_setprio(0);
 #pragma unroll
         for (int r4 = 0; r4 < 4; ++r4) {
           const f32x4_t d4 = *reinterpret_cast<lds_f4_t>(sl + (BQ + qb * 32 + 8 * r4) * 4);
@@ -581,6 +585,7 @@ attn_bwd_dkv_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ d
 #pragma unroll
         for (int tt = 0; tt < 2; ++tt) dsb[tt] = pack8(pacc, tt);
       }
+      __builtin_amdgcn_s_setprio(1);
       static_for<4>([&](auto dt_c) {
         TAW_CONST(dt, dt_c);
         static_for<2>([&](auto tt_c) {
@@ -591,6 +596,7 @@ attn_bwd_dkv_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ d
           dk[dt] = mfma(fq, dsb[tt], dk[dt]);
         });
       });
+      __builtin_amdgcn_s_setprio(0);
     });
   }
   __syncthreads();          // the ring becomes the output staging area
@@ -679,11 +685,13 @@ attn_bwd_dq_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dO
       f32x16_t sacc, pacc;
 #pragma unroll
       for (int r = 0; r < 16; ++r) { sacc[r] = 0.f; pacc[r] = 0.f; }
+      __builtin_amdgcn_s_setprio(1);
       static_for<8>([&](auto ks_c) {
         TAW_CONST(ks, ks_c);
         sacc = mfma(frag_nat2<ks, kb * 8192>(nat_t), qf[ks], sacc);
         pacc = mfma(frag_nat2<ks, kTileBytes + kb * 8192>(nat_t), dof[ks], pacc);
       });
+      __builtin_amdgcn_s_setprio(0);
       if (need_mask) {                                   // wavefront-uniform
         asm volatile("" ::: "memory");                   // keeps this a branch: most tiles skip the compares
 #pragma unroll
@@ -697,6 +705,7 @@ attn_bwd_dq_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dO
         const float p = fast_exp2(__builtin_fmaf(sacc[r], c, -l2));
         pacc[r] = p * (pacc[r] - dsum);
       }
+      __builtin_amdgcn_s_setprio(1);
       static_for<2>([&](auto t_c) {
         TAW_CONST(t, t_c);
         const bf16x8_t dsb = pack8(pacc, t);
@@ -707,6 +716,7 @@ attn_bwd_dq_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dO
           dq[dt] = mfma(fk, dsb, dq[dt]);
         });
       });
+      __builtin_amdgcn_s_setprio(0);
     });
   }
   __syncthreads();          // the ring becomes the output staging area
