@@ -254,6 +254,41 @@ def layer_fwd_rows(W, x, rows, n_heads, rope_theta=10000.0, rms_eps=1e-6):
     return hrow + swiglu_fwd(gu[:, :I], gu[:, I:]) @ W["w_down"].T
 
 
+def attention_fwd_rows(q_rows, k, v, rows):
+    """Attention output and log-sum-exp at selected query rows of one (batch, head).
+    q_rows: [n, d] (the queries at positions `rows`); k, v: [S, d].  Row t sees keys u <= t.
+    Returns o [n, d] and lse [n] = log sum_{u<=t} exp(q[t].k[u]/sqrt(d))."""
+    rows = np.asarray(rows)
+    S, d = k.shape
+    s = (q_rows @ k.T) / np.sqrt(d)
+    s = np.where(np.arange(S)[None, :] <= rows[:, None], s, -np.inf)
+    m = s.max(axis=1, keepdims=True)
+    e = np.exp(s - m)
+    z = e.sum(axis=1, keepdims=True)
+    return (e / z) @ v, (m + np.log(z))[:, 0]
+
+
+def attention_bwd_tail(q, k, v, do, t0):
+    """Gradients of attention_fwd for one (batch, head), restricted to what the queries t >= t0
+    determine completely: dq[t] for t >= t0 (a query's gradient needs only its own row of P) and
+    dk[u], dv[u] for u >= t0 (a key is seen by the queries t >= u only).  q, k, v, do: [S, d].
+    Returns dq [S-t0, d], dk [S-t0, d], dv [S-t0, d]."""
+    S, d = q.shape
+    scale = 1.0 / np.sqrt(d)
+    rows = np.arange(t0, S)
+    s = (q[t0:] @ k.T) * scale
+    s = np.where(np.arange(S)[None, :] <= rows[:, None], s, -np.inf)
+    e = np.exp(s - s.max(axis=1, keepdims=True))
+    P = e / e.sum(axis=1, keepdims=True)
+    o = P @ v
+    D = np.sum(do[t0:] * o, axis=1, keepdims=True)
+    dS = P * (do[t0:] @ v.T - D)
+    dq = (dS @ k) * scale
+    dk = (dS[:, t0:].T @ q[t0:]) * scale
+    dv = P[:, t0:].T @ do[t0:]
+    return dq, dk, dv
+
+
 def flops_fwd_bwd(B, S, H, I):
     """Model FLOPs of one forward+backward (counting convention, not arithmetic of the layer):
     GEMMs 6 T H (4H + 3I); attention 12 B (S(S+1)/2) H (causal pairs, backward = 2x forward)."""

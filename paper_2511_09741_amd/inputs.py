@@ -127,6 +127,19 @@ def make_weights(cfg: LayerConfig, seed: int = 0, layer: int = 0, sigma_w: float
     return {k: to_storage(v, cfg.dtype) for k, v in w.items()}
 
 
+def device_normal(shape, seed: int, std: float = 1.0, dtype=None):
+    """A seeded N(0, std) tensor drawn directly in GPU memory (for operands too large to draw on
+    the host and upload in a test): fp32 draws rounded once to `dtype` (torch.bfloat16 unless
+    given).  Both sides see the stored values: the HIP path reads the tensor, the oracle the
+    slices of it that are copied back."""
+    import torch
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(int(seed))
+    t = torch.empty(tuple(shape), dtype=torch.float32, device="cuda")
+    t.normal_(0.0, float(std), generator=gen)
+    return t.to(torch.bfloat16 if dtype is None else dtype)
+
+
 def weights_to_f64(w: dict, dtype: int) -> dict:
     return {k: to_f64(v, dtype) for k, v in w.items()}
 

@@ -417,3 +417,24 @@ def test_pins_catch_planted_mistakes(monkeypatch, mutation):
         monkeypatch.setattr(O, "_softmax_rows", lambda q, k, t0, sc: orig(q, k, t0, 1.0))
         with pytest.raises(AssertionError):
             test_softmax_scale_is_inv_sqrt_head_dim()
+
+
+def test_sampled_attention_matches_the_full_definition():
+    """attention_fwd_rows / attention_bwd_tail (used for full-size sampled parity) against the
+    complete attention_fwd / attention_bwd on a size where both run, plus lse against a direct sum."""
+    rng = np.random.default_rng(5)
+    S, d = 97, 8
+    q, k, v, do = (rng.standard_normal((1, S, 1, d)) for _ in range(4))
+    o = O.attention_fwd(q, k, v)
+    dq, dk, dv = O.attention_bwd(q, k, v, o, do)
+    rows = np.array([0, 1, 13, 50, 96])
+    o_r, lse = O.attention_fwd_rows(q[0, rows, 0], k[0, :, 0], v[0, :, 0], rows)
+    np.testing.assert_allclose(o_r, o[0, rows, 0], rtol=1e-12, atol=1e-14)
+    for n, t in enumerate(rows):
+        direct = np.log(np.sum(np.exp(k[0, :t + 1, 0] @ q[0, t, 0] / np.sqrt(d))))
+        assert abs(lse[n] - direct) < 1e-12
+    t0 = 60
+    dq_t, dk_t, dv_t = O.attention_bwd_tail(q[0, :, 0], k[0, :, 0], v[0, :, 0], do[0, :, 0], t0)
+    np.testing.assert_allclose(dq_t, dq[0, t0:, 0], rtol=1e-11, atol=1e-13)
+    np.testing.assert_allclose(dk_t, dk[0, t0:, 0], rtol=1e-11, atol=1e-13)
+    np.testing.assert_allclose(dv_t, dv[0, t0:, 0], rtol=1e-11, atol=1e-13)
