@@ -93,3 +93,104 @@ def test_bf16_layer_on_mfma_kernels(taw, B, S, nh, I_, sigma):
     tiles and leave ragged tails in tokens, widths and the SwiGLU dimension."""
     cfg = I.LayerConfig("bf16-mfma", I.BF16, B, S, nh * 128, nh, 128, I_, sigma_w=sigma)
     U.check_layer(taw, cfg, seed=B + S, gamma_jitter=0.1)
+
+
+def test_four_chained_layers_with_staged_weights(taw):
+    """Config 4's pattern at reduced width (bf16, MFMA kernels): forward through layers 0..3, backward
+    3..0, every layer's weights arriving through taw_weight_stage into one of two staging buffers on a
+    side stream (ready / consumed events).  The oracle chains the same four layers in fp64; the device
+    passes bf16 activations between layers.  Compared: the last output, the gradient of the first
+    input and all four gradient shards."""
+    import torch
+    from oracle import decoder_layer as O
+    nl = 4
+    cfg = I.LayerConfig("chain", I.BF16, 2, 320, 256, 2, 128, 392, sigma_w=0.05, n_layers=nl)
+    ws = [I.make_weights(cfg, 0, layer=l, gamma_jitter=0.1) for l in range(nl)]
+    x, dy = I.make_activations(cfg, 0)
+    # ---- oracle
+    w64 = [I.weights_to_f64(w, cfg.dtype) for w in ws]
+    a, caches = I.to_f64(x, cfg.dtype), []
+    for l in range(nl):
+        a, c = O.layer_fwd(w64[l], a, cfg.n_heads, cfg.rope_theta, cfg.rms_eps)
+        caches.append(c)
+    y_ref = a
+    g, G_ref = I.to_f64(dy, cfg.dtype), [None] * nl
+    for l in reversed(range(nl)):
+        g, G_ref[l] = O.layer_bwd(w64[l], caches[l], g)
+    dx_ref = g
+    # ---- device
+    desc = taw.desc_from_config(cfg, 0)
+    lay = taw.taw_layer_weight_layout(desc)
+    P = lay["total_elems"]
+    store = [U.to_dev(I.pack_chunk(w, lay, P, cfg.dtype), cfg.dtype) for w in ws]      # the owners' copies
+    stage = [torch.empty_like(store[0]) for _ in range(2)]
+    ctx = [torch.empty(taw.taw_layer_ctx_bytes(desc), dtype=torch.uint8, device="cuda") for _ in range(nl)]
+    wsb = taw.taw_layer_workspace_bytes(desc)
+    wsp = torch.empty(wsb, dtype=torch.uint8, device="cuda")
+    rope = torch.empty(cfg.S * (cfg.head_dim // 2) * 2, dtype=torch.float32, device="cuda")
+    taw.taw_rope_table_init(desc, rope)
+    G = [torch.zeros(P, dtype=torch.float32, device="cuda") for _ in range(nl)]
+    compute, side = torch.cuda.current_stream(), torch.cuda.Stream()
+    ready = [torch.cuda.Event() for _ in range(2)]
+    consumed = [torch.cuda.Event() for _ in range(2)]
+    order = list(range(nl)) + list(reversed(range(nl)))          # layer whose weights each step needs
+    for b in range(2):
+        consumed[b].record(compute)
+    taw.taw_weight_stage(stage[0], store[order[0]], P * 2, side, consumed[0], ready[0])
+    acts = [U.to_dev(x, cfg.dtype)]
+    grad = U.to_dev(dy, cfg.dtype)
+    for i, l in enumerate(order):
+        buf = i & 1
+        if i + 1 < len(order):                                    # next step's weights into the other buffer
+            taw.taw_weight_stage(stage[buf ^ 1], store[order[i + 1]], P * 2, side, consumed[buf ^ 1], ready[buf ^ 1])
+        compute.wait_event(ready[buf])
+        if i < nl:
+            y = torch.empty_like(acts[0])
+            taw.taw_layer_fwd(desc, stage[buf], rope, acts[l], y, ctx[l], wsp, wsb, compute)
+            acts.append(y)
+        else:
+            dx = torch.empty_like(grad)
+            taw.taw_layer_bwd(desc, stage[buf], rope, acts[l], grad, ctx[l], dx, G[l], wsp, wsb, compute)
+            grad = dx
+        consumed[buf].record(compute)
+    torch.cuda.synchronize()
+    e_y, e_dx = U.tensor_scale_err(U.from_dev(acts[nl]), y_ref), U.tensor_scale_err(U.from_dev(grad), dx_ref)
+    print(f"4 chained layers: y={e_y:.2e} dx={e_dx:.2e}", flush=True)
+    assert e_y < 2e-2 and e_dx < 2e-2
+    for l in range(nl):
+        got = {k: v.astype(np.float64) for k, v in I.unpack_shard(G[l].cpu().numpy(), lay, cfg).items()}
+        for k in G_ref[l]:
+            e = U.tensor_scale_err(got[k], G_ref[l][k])
+            assert e < 2e-2, (l, k, e)
+
+
+def test_bf16_microbatch_accumulation_with_staging(taw):
+    """Config 5's pattern at reduced width (bf16, MFMA kernels): one layer, four micro-batches, the
+    weight gradients accumulated by the backward's epilogue into the fp32 shard, while the next
+    layer's chunk is staged on a side stream."""
+    import torch
+    from oracle import decoder_layer as O
+    cfg = I.LayerConfig("mb4", I.BF16, 1, 384, 256, 2, 128, 520, sigma_w=0.05, n_microbatches=4)
+    w = I.make_weights(cfg, 0, gamma_jitter=0.1)
+    w64 = I.weights_to_f64(w, cfg.dtype)
+    L = U.DeviceLayer(taw, cfg, flags=taw.TAW_ACCUMULATE)
+    L.set_weights(w)
+    nxt = U.to_dev(I.pack_chunk(I.make_weights(cfg, 0, layer=1), L.layout, L.layout["total_elems"], cfg.dtype), cfg.dtype)
+    staged = torch.empty_like(nxt)
+    side = torch.cuda.Stream()
+    taw.taw_weight_stage(staged, nxt, nxt.numel() * 2, side, None, None)
+    Gsum = None
+    for mb in range(4):
+        x, dy = I.make_activations(cfg, 0, mb=mb)
+        xd, dyd = U.to_dev(x, cfg.dtype), U.to_dev(dy, cfg.dtype)
+        y = L.fwd(xd)
+        dx = L.bwd(xd, dyd)
+        yr, cache = O.layer_fwd(w64, I.to_f64(x, cfg.dtype), cfg.n_heads, cfg.rope_theta, cfg.rms_eps)
+        dxr, G = O.layer_bwd(w64, cache, I.to_f64(dy, cfg.dtype))
+        assert U.tensor_scale_err(U.from_dev(y), yr) < 2e-2 and U.tensor_scale_err(U.from_dev(dx), dxr) < 2e-2
+        Gsum = G if Gsum is None else {k: O.grad_accum(Gsum[k], G[k]) for k in G}
+    got = L.grads()
+    for k in Gsum:
+        assert U.tensor_scale_err(got[k], Gsum[k]) < 2e-2, k
+    torch.cuda.synchronize()
+    assert torch.equal(staged, nxt)
