@@ -54,6 +54,11 @@ typedef enum { TAW_F32 = 0, TAW_BF16 = 1 } taw_dtype;
 /* flags of taw_layer_desc */
 #define TAW_ACCUMULATE 1u /* taw_layer_bwd adds the weight gradients into G_shard (G += dW);
                              without it the call overwrites the shard (G = dW) */
+#define TAW_RECOMPUTE 2u  /* activation checkpointing, the mode the paper trains in ("Experimental
+                             Setup"): the forward keeps nothing but its input x (ctx is unused and may
+                             be NULL, taw_layer_ctx_bytes() is 0); the backward first rebuilds the
+                             layer's intermediates from x inside the workspace, which is larger by
+                             what ctx would have held.  Same results, about 4/3 of the arithmetic. */
 
 /* One decoder layer and the micro-batch it is applied to (B, S, H as in the paper's Table 1). */
 typedef struct {
@@ -66,7 +71,7 @@ typedef struct {
   int32_t I;          /* SwiGLU intermediate width */
   float rope_theta;   /* rotary base, 10000 for LLaMA-2 */
   float rms_eps;      /* added to the mean of squares inside the square root */
-  uint32_t flags;     /* TAW_ACCUMULATE */
+  uint32_t flags;     /* TAW_ACCUMULATE | TAW_RECOMPUTE */
 } taw_layer_desc;
 
 /* Element offsets of the sub-tensors inside the flat weight chunk W_j (the unit that is moved

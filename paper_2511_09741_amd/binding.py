@@ -14,6 +14,7 @@ LIB_PATH = os.path.join(_HERE, "libtaw.so")
 
 TAW_F32, TAW_BF16 = 0, 1
 TAW_ACCUMULATE = 1
+TAW_RECOMPUTE = 2
 TAW_IMPL_AUTO, TAW_IMPL_GENERIC, TAW_IMPL_MFMA = 0, 1, 2
 TAW_GEMM_NT, TAW_GEMM_NN, TAW_GEMM_TN = 0, 1, 2
 TAW_OK = 0

@@ -62,7 +62,7 @@ static int check_desc(const taw_layer_desc* d) {
   if ((int64_t)d->B * d->S > (int64_t)1 << 24) return fail(TAW_ERR_SHAPE, "B*S=%lld exceeds 2^24 tokens", (long long)d->B * d->S);
   if (!(d->rms_eps >= 0.f)) return fail(TAW_ERR_SHAPE, "rms_eps must be >= 0");
   if (!(d->rope_theta > 0.f)) return fail(TAW_ERR_SHAPE, "rope_theta must be > 0");
-  if (d->flags & ~TAW_ACCUMULATE) return fail(TAW_ERR_SHAPE, "unknown flag bits 0x%x", d->flags);
+  if (d->flags & ~(TAW_ACCUMULATE | TAW_RECOMPUTE)) return fail(TAW_ERR_SHAPE, "unknown flag bits 0x%x", d->flags);
   return TAW_OK;
 }
 
@@ -137,13 +137,20 @@ static Work carve_work(const taw_layer_desc* d, void* base) {
   return w;
 }
 
+// With TAW_RECOMPUTE nothing is kept between the calls: the forward's intermediates live in the
+// workspace, in front of the backward's scratch, and the backward rebuilds them there first.
+static size_t ctx_bytes_of(const taw_layer_desc* d) { return (d->flags & TAW_RECOMPUTE) ? 0 : carve_ctx(d, nullptr).bytes; }
+static size_t workspace_bytes_of(const taw_layer_desc* d) {
+  return carve_work(d, nullptr).bytes + ((d->flags & TAW_RECOMPUTE) ? carve_ctx(d, nullptr).bytes : 0);
+}
+
 extern "C" size_t taw_layer_ctx_bytes(const taw_layer_desc* desc) {
   if (check_desc(desc)) return 0;
-  return carve_ctx(desc, nullptr).bytes;
+  return ctx_bytes_of(desc);
 }
 extern "C" size_t taw_layer_workspace_bytes(const taw_layer_desc* desc) {
   if (check_desc(desc)) return 0;
-  return carve_work(desc, nullptr).bytes;
+  return workspace_bytes_of(desc);
 }
 
 // ------------------------------------------------------------------------------ op dispatch helpers
@@ -167,27 +174,12 @@ extern "C" int taw_rope_table_init(const taw_layer_desc* desc, float* rope_table
 }
 
 // ------------------------------------------------------------------------------ forward
-extern "C" int taw_layer_fwd(const taw_layer_desc* desc, const void* W_chunk, const float* rope_table, const void* x, void* y,
-                             void* ctx, void* workspace, size_t workspace_bytes, void* stream) {
-  int rc = check_desc(desc);
-  if (rc) return rc;
-  TAW_REQUIRE_PTR(W_chunk); TAW_REQUIRE_PTR(rope_table); TAW_REQUIRE_PTR(x); TAW_REQUIRE_PTR(y); TAW_REQUIRE_PTR(ctx);
-  TAW_REQUIRE_PTR(workspace);
-  TAW_REQUIRE_ALIGNED(W_chunk); TAW_REQUIRE_ALIGNED(rope_table); TAW_REQUIRE_ALIGNED(x); TAW_REQUIRE_ALIGNED(y);
-  TAW_REQUIRE_ALIGNED(ctx); TAW_REQUIRE_ALIGNED(workspace);
-  if (x == y) return fail(TAW_ERR_SHAPE, "y must not alias x");
-  if (workspace_bytes < carve_work(desc, nullptr).bytes)
-    return fail(TAW_ERR_WORKSPACE, "workspace_bytes=%zu < required %zu", workspace_bytes, carve_work(desc, nullptr).bytes);
-  Plan p;
-  rc = make_plan(desc, &p);
-  if (rc) return rc;
-  taw_weight_layout L;
-  taw_layer_weight_layout(desc, &L);
-  const hipStream_t st = (hipStream_t)stream;
+// The forward's kernel sequence into the intermediates `c`; y == nullptr stops after the SwiGLU
+// (all the backward needs when it rebuilds the intermediates).
+static int run_fwd(const taw_layer_desc* desc, const Plan& p, const taw_weight_layout& L, const void* W_chunk, const float* rope_table,
+                   const void* x, void* y, const Ctx& c, hipStream_t st) {
   const int dt = desc->dtype;
   const int64_t T = (int64_t)desc->B * desc->S, H = desc->H, I = desc->I;
-  const Ctx c = carve_ctx(desc, ctx);
-
   // xn = rmsnorm(x; gamma_attn)
   TAW_LAUNCH(launch_rmsnorm_fwd(dt, T, (int)H, x, at(W_chunk, L.gamma_attn, dt), desc->rms_eps, c.xn, c.r1, st), "rmsnorm_fwd(attn)");
   // qkv = xn Wqkv^T
@@ -205,8 +197,29 @@ extern "C" int taw_layer_fwd(const taw_layer_desc* desc, const void* W_chunk, co
   TAW_LAUNCH(gemm(p, dt, GEMM_NT, T, 2 * I, H, c.hn, H, at(W_chunk, L.w_gate_up, dt), H, c.gu, 2 * I, dt, 0, nullptr, 0, st), "gemm gate/up");
   TAW_LAUNCH(launch_swiglu_fwd(dt, T, (int)I, c.gu, c.a, st), "swiglu_fwd");
   // y = h + a Wd^T
-  TAW_LAUNCH(gemm(p, dt, GEMM_NT, T, H, I, c.a, I, at(W_chunk, L.w_down, dt), I, y, H, dt, 0, c.h, H, st), "gemm down");
+  if (y) TAW_LAUNCH(gemm(p, dt, GEMM_NT, T, H, I, c.a, I, at(W_chunk, L.w_down, dt), I, y, H, dt, 0, c.h, H, st), "gemm down");
   return TAW_OK;
+}
+
+extern "C" int taw_layer_fwd(const taw_layer_desc* desc, const void* W_chunk, const float* rope_table, const void* x, void* y,
+                             void* ctx, void* workspace, size_t workspace_bytes, void* stream) {
+  int rc = check_desc(desc);
+  if (rc) return rc;
+  const bool recompute = (desc->flags & TAW_RECOMPUTE) != 0;
+  TAW_REQUIRE_PTR(W_chunk); TAW_REQUIRE_PTR(rope_table); TAW_REQUIRE_PTR(x); TAW_REQUIRE_PTR(y);
+  if (!recompute) TAW_REQUIRE_PTR(ctx);
+  TAW_REQUIRE_PTR(workspace);
+  TAW_REQUIRE_ALIGNED(W_chunk); TAW_REQUIRE_ALIGNED(rope_table); TAW_REQUIRE_ALIGNED(x); TAW_REQUIRE_ALIGNED(y);
+  TAW_REQUIRE_ALIGNED(ctx); TAW_REQUIRE_ALIGNED(workspace);
+  if (x == y) return fail(TAW_ERR_SHAPE, "y must not alias x");
+  if (workspace_bytes < workspace_bytes_of(desc))
+    return fail(TAW_ERR_WORKSPACE, "workspace_bytes=%zu < required %zu", workspace_bytes, workspace_bytes_of(desc));
+  Plan p;
+  rc = make_plan(desc, &p);
+  if (rc) return rc;
+  taw_weight_layout L;
+  taw_layer_weight_layout(desc, &L);
+  return run_fwd(desc, p, L, W_chunk, rope_table, x, y, carve_ctx(desc, recompute ? workspace : ctx), (hipStream_t)stream);
 }
 
 // ------------------------------------------------------------------------------ backward
@@ -214,13 +227,15 @@ extern "C" int taw_layer_bwd(const taw_layer_desc* desc, const void* W_chunk, co
                              const void* ctx, void* dx, float* G_shard, void* workspace, size_t workspace_bytes, void* stream) {
   int rc = check_desc(desc);
   if (rc) return rc;
-  TAW_REQUIRE_PTR(W_chunk); TAW_REQUIRE_PTR(rope_table); TAW_REQUIRE_PTR(x); TAW_REQUIRE_PTR(dy); TAW_REQUIRE_PTR(ctx);
+  const bool recompute = (desc->flags & TAW_RECOMPUTE) != 0;
+  TAW_REQUIRE_PTR(W_chunk); TAW_REQUIRE_PTR(rope_table); TAW_REQUIRE_PTR(x); TAW_REQUIRE_PTR(dy);
+  if (!recompute) TAW_REQUIRE_PTR(ctx);
   TAW_REQUIRE_PTR(dx); TAW_REQUIRE_PTR(G_shard); TAW_REQUIRE_PTR(workspace);
   TAW_REQUIRE_ALIGNED(W_chunk); TAW_REQUIRE_ALIGNED(rope_table); TAW_REQUIRE_ALIGNED(x); TAW_REQUIRE_ALIGNED(dy);
   TAW_REQUIRE_ALIGNED(ctx); TAW_REQUIRE_ALIGNED(dx); TAW_REQUIRE_ALIGNED(G_shard); TAW_REQUIRE_ALIGNED(workspace);
   if (dx == dy || dx == x) return fail(TAW_ERR_SHAPE, "dx must not alias dy or x");
-  if (workspace_bytes < carve_work(desc, nullptr).bytes)
-    return fail(TAW_ERR_WORKSPACE, "workspace_bytes=%zu < required %zu", workspace_bytes, carve_work(desc, nullptr).bytes);
+  if (workspace_bytes < workspace_bytes_of(desc))
+    return fail(TAW_ERR_WORKSPACE, "workspace_bytes=%zu < required %zu", workspace_bytes, workspace_bytes_of(desc));
   Plan p;
   rc = make_plan(desc, &p);
   if (rc) return rc;
@@ -230,8 +245,13 @@ extern "C" int taw_layer_bwd(const taw_layer_desc* desc, const void* W_chunk, co
   const int dt = desc->dtype;
   const int acc = (desc->flags & TAW_ACCUMULATE) ? 1 : 0;
   const int64_t T = (int64_t)desc->B * desc->S, H = desc->H, I = desc->I;
-  const Ctx c = carve_ctx(desc, const_cast<void*>(ctx));
-  const Work w = carve_work(desc, workspace);
+  // the saved intermediates, or (TAW_RECOMPUTE) the front of the workspace, rebuilt here from x
+  const Ctx c = carve_ctx(desc, recompute ? workspace : const_cast<void*>(ctx));
+  const Work w = carve_work(desc, static_cast<char*>(workspace) + (recompute ? c.bytes : 0));
+  if (recompute) {
+    rc = run_fwd(desc, p, L, W_chunk, rope_table, x, nullptr, c, st);
+    if (rc) return rc;
+  }
 
   // y = h + a Wd^T :  da = dy Wd ;  G.Wd (+)= dy^T a
   TAW_LAUNCH(gemm(p, dt, GEMM_NN, T, I, H, dy, H, at(W_chunk, L.w_down, dt), I, w.da, I, dt, 0, nullptr, 0, st), "gemm da");

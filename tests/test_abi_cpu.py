@@ -74,6 +74,19 @@ def test_ctx_and_workspace_sizes(lib):
     assert taw.taw_layer_ctx_bytes(bad) == 0 and taw.taw_layer_workspace_bytes(bad) == 0
 
 
+def test_recompute_mode_moves_the_cache_into_the_workspace(lib):
+    """TAW_RECOMPUTE: nothing is kept between forward and backward; the workspace grows by exactly
+    what the cache would have held, and the calls insist on that size before launching anything."""
+    cfg = I.CONFIGS["C2"]
+    d0, d1 = taw.desc_from_config(cfg), taw.desc_from_config(cfg, taw.TAW_RECOMPUTE)
+    assert taw.taw_layer_ctx_bytes(d1) == 0
+    assert taw.taw_layer_workspace_bytes(d1) == taw.taw_layer_workspace_bytes(d0) + taw.taw_layer_ctx_bytes(d0)
+    ok = 0x10000
+    with pytest.raises(taw.TawError) as e:
+        taw.taw_layer_bwd(d1, ok, ok, ok, ok + 4096, None, ok + 8192, ok, ok, taw.taw_layer_workspace_bytes(d0))
+    assert e.value.status == taw.TAW_ERR_WORKSPACE       # ctx may be NULL, the workspace may not be the small one
+
+
 @pytest.mark.parametrize("kw,code", [
     (dict(H=100), taw.TAW_ERR_SHAPE), (dict(S=0), taw.TAW_ERR_SHAPE), (dict(B=-1), taw.TAW_ERR_SHAPE),
     (dict(dtype=7), taw.TAW_ERR_DTYPE), (dict(head_dim=15, n_heads=4, H=60), taw.TAW_ERR_SHAPE),

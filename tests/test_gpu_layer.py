@@ -194,3 +194,33 @@ def test_bf16_microbatch_accumulation_with_staging(taw):
         assert U.tensor_scale_err(got[k], Gsum[k]) < 2e-2, k
     torch.cuda.synchronize()
     assert torch.equal(staged, nxt)
+
+
+@pytest.mark.parametrize("cfg", [I.CONFIGS["C1"], I.LayerConfig("recompute-bf16", I.BF16, 2, 333, 256, 2, 128, 392, sigma_w=0.05)],
+                         ids=["fp32", "bf16"])
+def test_recompute_mode_gives_the_same_results(taw, cfg):
+    """Activation checkpointing (TAW_RECOMPUTE): the forward keeps only x, the backward rebuilds the
+    intermediates in the workspace.  Results against the oracle as in the default mode, and bit-identical
+    to the default mode's own results (the same kernels on the same values)."""
+    import torch
+    w = I.make_weights(cfg, 3, gamma_jitter=0.1)
+    x, dy = I.make_activations(cfg, 3)
+    xd, dyd = U.to_dev(x, cfg.dtype), U.to_dev(dy, cfg.dtype)
+    outs = []
+    for flags in (0, taw.TAW_RECOMPUTE):
+        L = U.DeviceLayer(taw, cfg, flags=flags)
+        L.set_weights(w)
+        y = L.fwd(xd)
+        L.ws.fill_(0x5A)                    # nothing of the forward may survive in the workspace
+        dx = L.bwd(xd, dyd)
+        torch.cuda.synchronize()
+        outs.append((y, dx, L.G.clone()))
+    assert taw.taw_layer_ctx_bytes(taw.desc_from_config(cfg, taw.TAW_RECOMPUTE)) == 0
+    for a, b in zip(outs[0], outs[1]):
+        assert torch.equal(a, b)
+    w64 = I.weights_to_f64(w, cfg.dtype)
+    from oracle import decoder_layer as O
+    yr, cache = O.layer_fwd(w64, I.to_f64(x, cfg.dtype), cfg.n_heads, cfg.rope_theta, cfg.rms_eps)
+    dxr, _ = O.layer_bwd(w64, cache, I.to_f64(dy, cfg.dtype))
+    assert U.tensor_scale_err(U.from_dev(outs[1][0]), yr) < U.TOL[cfg.dtype]
+    assert U.tensor_scale_err(U.from_dev(outs[1][1]), dxr) < U.TOL[cfg.dtype]
