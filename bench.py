@@ -20,6 +20,7 @@ Prints ONE JSON line.  Besides the contract fields it carries
   cpu_baseline  the fp64 CPU oracle timed on this machine's host cores on a bounded sample
   kernels       per-kernel-class rates measured the same way (attention, bandwidth kernels)
   overlap       step time with and without the staging copy running beside it
+  recompute     the same step in activation-checkpointing mode (TAW_RECOMPUTE): same model FLOPs
 """
 from __future__ import annotations
 
@@ -35,6 +36,10 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0
+# HBM-side bytes per GEMM launch (average of the 12 shapes of a step), from two rocprofv3 --pmc runs of this file
+# (FETCH_SIZE, WRITE_SIZE; each scaled by what the counter reads for the staging copy kernel, a plain copy of
+# known size): profiles/gemm_C2_hbm_traffic.md.  Only measured for the workload named.
+GEMM_TRAFFIC_BYTES_PER_LAUNCH = {"C2": 1465.9e6}
 
 
 def model_flops(cfg):
@@ -52,6 +57,7 @@ def main():
     ap.add_argument("--workload", default="C2", choices=["C2", "C3", "C4", "C5"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-leg", action="store_true")
+    ap.add_argument("--no-recompute-leg", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only (one device's share of the weight pipeline); "
@@ -87,8 +93,10 @@ def main():
     g_local = torch.zeros(P, dtype=torch.float32, device="cuda")
     G_shard = torch.zeros(P, dtype=torch.float32, device="cuda")
     ctx = torch.empty(taw.taw_layer_ctx_bytes(desc_acc), dtype=torch.uint8, device="cuda")
+    desc_rc = taw.desc_from_config(cfg, taw.TAW_RECOMPUTE)      # activation checkpointing (extra leg below)
+    ws_bytes_rc = taw.taw_layer_workspace_bytes(desc_rc)
     ws_bytes = taw.taw_layer_workspace_bytes(desc_acc)
-    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+    ws = torch.empty(ws_bytes if args.no_recompute_leg else ws_bytes_rc, dtype=torch.uint8, device="cuda")
     rope = torch.empty(cfg.S * (cfg.head_dim // 2) * 2, dtype=torch.float32, device="cuda")
     taw.taw_rope_table_init(desc_acc, rope)
 
@@ -148,6 +156,24 @@ def main():
                "delta_frac": round(ms_stage / ms_nostage - 1.0, 4), "copy_alone_ms": round(copy_ms, 4),
                "copy_alone_GBs": round(2 * chunk_bytes / copy_ms / 1e6, 1)}
 
+    # ---- activation-checkpointing mode: same model FLOPs, the backward re-runs the forward first
+    recompute = None
+    if not args.no_recompute_leg:
+        def step_rc():
+            taw.taw_layer_fwd(desc_rc, stage_buf[0], rope, x, y, None, ws, ws_bytes_rc, compute)
+            taw.taw_layer_bwd(desc_rc, stage_buf[0], rope, x, dy, None, dx, g_local, ws, ws_bytes_rc, compute)
+            taw.taw_grad_accum(G_shard, g_local, taw.TAW_F32, P, 1.0, compute)
+        step_rc()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        n_rc = max(3, args.steps // 2)
+        for _ in range(n_rc):
+            step_rc()
+        torch.cuda.synchronize()
+        ms_rc = (time.perf_counter() - t0) * 1e3 / n_rc
+        recompute = {"ms_per_step": round(ms_rc, 4), "model_TFLOPs": round(flops / ms_rc / 1e9, 2),
+                     "ctx_bytes_saved": int(taw.taw_layer_ctx_bytes(desc_acc))}
+
     # ---- per-kernel leg: HIP events on the launch stream around each launch
     def ev_time(fn, reps=5):
         fn()
@@ -194,7 +220,9 @@ def main():
         achieved = tot_fl / tot_ms / 1e9
         roofline = {"kernel": "gemm_mfma_kernel (bf16 MFMA GEMM, 12 launches per step)", "bound": "mfma",
                     "achieved": round(achieved, 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                    "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": None,
+                    "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": GEMM_TRAFFIC_BYTES_PER_LAUNCH.get(args.workload),
+                    "traffic_unit": "bytes per launch (L2 fills + write-backs, rocprofv3 FETCH_SIZE/WRITE_SIZE)",
+                    "algorithmic_bytes_per_launch": sum((M * K + N * K) * 2 + M * N * (4 if cd == F32 else 2) for (_, _, M, N, K, *_r, cd) in gemms) / len(gemms),
                     "avg_launch_ms": round(tot_ms / len(gemms), 4), "flops_per_launch_avg": tot_fl / len(gemms)}
         kernels["gemm"] = per
         # attention
@@ -255,7 +283,7 @@ def main():
         "config": {"workload": f"{cfg.name}: bf16 decoder layer fwd+bwd, B={cfg.B} S={cfg.S} H={cfg.H} heads={cfg.n_heads}x{cfg.head_dim} "
                                f"I={cfg.I}, + weight staging on a side stream + fp32 grad-shard accumulation",
                    "model_flops_per_step": flops, "frac_of_bf16_mfma_peak": round(value / PEAK_BF16_TFLOPS, 4)},
-        "roofline": roofline, "cpu_baseline": cpu, "kernels": kernels, "overlap": overlap,
+        "roofline": roofline, "cpu_baseline": cpu, "kernels": kernels, "overlap": overlap, "recompute": recompute,
     }
     print(json.dumps(out))
 
