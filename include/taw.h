@@ -135,6 +135,24 @@ int taw_grad_accum(float* G_dst, const void* g_src, int32_t src_dtype, size_t n_
 int taw_weight_stage(void* dst_buf, const void* src_shard, size_t bytes, void* copy_stream,
                      void* wait_event, void* ready_event);
 
+/* Owner-side update of a weight shard from its aggregated gradient shard ("updates are applied
+ * locally using colocated optimizer states", Methodology, Group-Based Weight Pipeline Scheduler).
+ * The paper does not name the optimizer; this is AdamW (decoupled weight decay), one pass over the
+ * shard, for step number `step` (1-based):
+ *   g = grad_scale * G[i];  m = beta1 m + (1-beta1) g;  v = beta2 v + (1-beta2) g^2;
+ *   w = w - lr * ( (m / (1-beta1^step)) / (sqrt(v / (1-beta2^step)) + eps) + weight_decay * w )
+ * master, m, v, G_shard are fp32 arrays of n_elems (the optimizer state colocated with the shard);
+ * W_chunk (chunk_dtype, n_elems) receives w rounded to the storage type, ready to be passed on.
+ * grad_scale carries the 1/N of micro-batch averaging.  zero_grad != 0 leaves G_shard zeroed for the
+ * next mini-batch.  n_elems == 0 is a no-op.  The arrays must not overlap. */
+typedef struct {
+  float lr, beta1, beta2, eps, weight_decay, grad_scale;
+  int32_t step;       /* >= 1 */
+  int32_t zero_grad;
+} taw_adamw_desc;
+int taw_optimizer_step(const taw_adamw_desc* opt, void* W_chunk, int32_t chunk_dtype, float* master, float* m,
+                       float* v, float* G_shard, size_t n_elems, void* stream);
+
 /* Name of a status code (static string), and a description of the most recent error on the
  * calling thread (valid until the next failing call on that thread). */
 const char* taw_status_string(int status);

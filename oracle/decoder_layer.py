@@ -219,6 +219,21 @@ def grad_accum(G_dst, g_src, scale=1.0):
     return G_dst + scale * g_src
 
 
+def adamw_step(w, m, v, g, step, lr, beta1, beta2, eps, weight_decay, grad_scale=1.0):
+    """Owner-side update of a shard (Methodology, GWPS: "updates are applied locally using colocated
+    optimizer states"; the optimizer itself is not named by the paper: AdamW with decoupled weight
+    decay is the reading adopted).  All arrays fp64; step is 1-based.  Returns (w, m, v) after the step:
+      g' = grad_scale g;  m = b1 m + (1-b1) g';  v = b2 v + (1-b2) g'^2
+      w = w - lr ( m/(1-b1^t) / (sqrt(v/(1-b2^t)) + eps) + weight_decay w )"""
+    g = grad_scale * g
+    m = beta1 * m + (1.0 - beta1) * g
+    v = beta2 * v + (1.0 - beta2) * g * g
+    mh = m / (1.0 - beta1 ** step)
+    vh = v / (1.0 - beta2 ** step)
+    w = w - lr * (mh / (np.sqrt(vh) + eps) + weight_decay * w)
+    return w, m, v
+
+
 # ----------------------------------------------------------------------------- sampled evaluation
 def layer_fwd_rows(W, x, rows, n_heads, rope_theta=10000.0, rms_eps=1e-6):
     """y at selected token rows of ONE batch element, by the same definition.

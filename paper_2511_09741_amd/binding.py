@@ -33,6 +33,11 @@ class taw_weight_layout(C.Structure):
     _fields_ = [(f, C.c_size_t) for f in LAYOUT_FIELDS]
 
 
+class taw_adamw_desc(C.Structure):
+    _fields_ = [("lr", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float), ("eps", C.c_float),
+                ("weight_decay", C.c_float), ("grad_scale", C.c_float), ("step", C.c_int32), ("zero_grad", C.c_int32)]
+
+
 class TawError(RuntimeError):
     def __init__(self, status: int, name: str, detail: str):
         super().__init__(f"{name} ({status}): {detail}")
@@ -52,6 +57,7 @@ _SIGS = {
     "taw_layer_bwd": (C.c_int, [_dp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
     "taw_grad_accum": (C.c_int, [_vp, _vp, _i32, _sz, _f, _vp]),
     "taw_weight_stage": (C.c_int, [_vp, _vp, _sz, _vp, _vp, _vp]),
+    "taw_optimizer_step": (C.c_int, [C.POINTER(taw_adamw_desc), _vp, _i32, _vp, _vp, _vp, _vp, _sz, _vp]),
     "taw_status_string": (C.c_char_p, [C.c_int]),
     "taw_last_error": (C.c_char_p, []),
     "taw_op_gemm": (C.c_int, [_i32, _i32, _i64, _i64, _i64, _vp, _i64, _vp, _i64, _vp, _i64, _i32, _i32, _vp, _i64, _i32, _vp]),
@@ -148,6 +154,13 @@ def taw_layer_bwd(desc, W_chunk, rope_table, x, dy, ctx, dx, G_shard, workspace,
         workspace_bytes = workspace.numel() * workspace.element_size()
     _check(load().taw_layer_bwd(C.byref(desc), _p(W_chunk), _p(rope_table), _p(x), _p(dy), _p(ctx), _p(dx), _p(G_shard),
                                 _p(workspace), workspace_bytes, _stream(stream)))
+
+
+def taw_optimizer_step(W_chunk, chunk_dtype, master, m, v, G_shard, n_elems, step, lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8,
+                       weight_decay=0.0, grad_scale=1.0, zero_grad=False, stream=None):
+    d = taw_adamw_desc(lr, beta1, beta2, eps, weight_decay, grad_scale, step, int(zero_grad))
+    _check(load().taw_optimizer_step(C.byref(d), _p(W_chunk), chunk_dtype, _p(master), _p(m), _p(v), _p(G_shard), n_elems,
+                                     _stream(stream)))
 
 
 def taw_grad_accum(G_dst, g_src, src_dtype, n_elems, scale=1.0, stream=None):

@@ -299,6 +299,58 @@ __global__ void __launch_bounds__(256) grad_accum_kernel(float* __restrict__ G, 
   }
 }
 
+// =============================================================================== owner-side optimizer step
+// AdamW with decoupled weight decay over a whole shard, one pass: reads G, m, v and the fp32 master
+// weights, writes m, v, the master weights and the weight chunk in its storage type; optionally
+// leaves G zeroed for the next mini-batch.  b1c = 1 - beta1^t, b2c = 1 - beta2^t come from the host.
+template <typename TW>
+__global__ void __launch_bounds__(256) adamw_kernel(TW* __restrict__ chunk, float* __restrict__ master, float* __restrict__ m,
+                                                     float* __restrict__ v, float* __restrict__ G, size_t n, float lr, float beta1,
+                                                     float beta2, float eps, float wd, float b1c, float b2c, float gscale,
+                                                     int zero_grad) {
+  const size_t nvec = n / 4;
+  const size_t stride = (size_t)gridDim.x * 256;
+  auto upd = [&](float g, float& mm, float& vv, float& w) {
+    g *= gscale;
+    mm = beta1 * mm + (1.f - beta1) * g;
+    vv = beta2 * vv + (1.f - beta2) * g * g;
+    const float mh = mm / b1c, vh = vv / b2c;
+    w = w - lr * (mh / (sqrtf(vh) + eps) + wd * w);
+  };
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < nvec; i += stride) {
+    f32x4_t g4 = *reinterpret_cast<const f32x4_t*>(G + 4 * i);
+    f32x4_t m4 = *reinterpret_cast<const f32x4_t*>(m + 4 * i);
+    f32x4_t v4 = *reinterpret_cast<const f32x4_t*>(v + 4 * i);
+    f32x4_t w4 = *reinterpret_cast<const f32x4_t*>(master + 4 * i);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      float mm = m4[j], vv = v4[j], w = w4[j];
+      upd(g4[j], mm, vv, w);
+      m4[j] = mm; v4[j] = vv; w4[j] = w;
+    }
+    *reinterpret_cast<f32x4_t*>(m + 4 * i) = m4;
+    *reinterpret_cast<f32x4_t*>(v + 4 * i) = v4;
+    *reinterpret_cast<f32x4_t*>(master + 4 * i) = w4;
+    if constexpr (sizeof(TW) == 4) {
+      *reinterpret_cast<f32x4_t*>(chunk + 4 * i) = w4;
+    } else {
+      bf16x4_t o;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) o[j] = (bf16_t)w4[j];
+      *reinterpret_cast<bf16x4_t*>(chunk + 4 * i) = o;
+    }
+    if (zero_grad) *reinterpret_cast<f32x4_t*>(G + 4 * i) = f32x4_t{0.f, 0.f, 0.f, 0.f};
+  }
+  if (blockIdx.x == 0 && threadIdx.x < (n & 3)) {
+    const size_t i = nvec * 4 + threadIdx.x;
+    float mm = m[i], vv = v[i], w = master[i];
+    upd(G[i], mm, vv, w);
+    m[i] = mm; v[i] = vv; master[i] = w;
+    chunk[i] = (TW)w;
+    if (zero_grad) G[i] = 0.f;
+  }
+}
+
 // =============================================================================== staging copy
 // HBM-to-HBM copy of a weight chunk.  A modest grid on purpose: it runs beside the layer's
 // compute kernels on another stream and should take few compute units away from them.
@@ -480,6 +532,19 @@ int launch_grad_accum(float* G, const void* g, int src_dtype, size_t n, float sc
   const unsigned grid = (unsigned)(want > 8192 ? 8192 : want);
   if (src_dtype == DT_BF16) hipLaunchKernelGGL((grad_accum_kernel<bf16_t>), dim3(grid), dim3(256), 0, st, G, (const bf16_t*)g, n, scale);
   else hipLaunchKernelGGL((grad_accum_kernel<float>), dim3(grid), dim3(256), 0, st, G, (const float*)g, n, scale);
+  return last_err();
+}
+
+int launch_adamw(int w_dtype, void* chunk, float* master, float* m, float* v, float* G, size_t n, float lr, float beta1, float beta2,
+                 float eps, float wd, float b1c, float b2c, float gscale, int zero_grad, hipStream_t st) {
+  if (n == 0) return 0;
+  size_t want = (n / 4 + 255) / 256;
+  if (want == 0) want = 1;
+  const unsigned grid = (unsigned)(want > 8192 ? 8192 : want);
+  if (w_dtype == DT_BF16)
+    hipLaunchKernelGGL((adamw_kernel<bf16_t>), dim3(grid), dim3(256), 0, st, (bf16_t*)chunk, master, m, v, G, n, lr, beta1, beta2, eps, wd, b1c, b2c, gscale, zero_grad);
+  else
+    hipLaunchKernelGGL((adamw_kernel<float>), dim3(grid), dim3(256), 0, st, (float*)chunk, master, m, v, G, n, lr, beta1, beta2, eps, wd, b1c, b2c, gscale, zero_grad);
   return last_err();
 }
 

@@ -5,6 +5,7 @@
 #include <cstdio>
 #include <cstring>
 #include <cstdarg>
+#include <cmath>
 
 #include "../../include/taw.h"
 #include "../../include/taw_ops.h"
@@ -293,6 +294,28 @@ extern "C" int taw_grad_accum(float* G_dst, const void* g_src, int32_t src_dtype
   const char* b = static_cast<const char*>(g_src);
   if (a < b + n_elems * dt_size(src_dtype) && b < a + n_elems * 4) return fail(TAW_ERR_SHAPE, "G_dst and g_src overlap");
   TAW_LAUNCH(launch_grad_accum(G_dst, g_src, src_dtype, n_elems, scale, (hipStream_t)stream), "grad_accum kernel");
+  return TAW_OK;
+}
+
+extern "C" int taw_optimizer_step(const taw_adamw_desc* opt, void* W_chunk, int32_t chunk_dtype, float* master, float* m, float* v,
+                                  float* G_shard, size_t n_elems, void* stream) {
+  if (!opt) return fail(TAW_ERR_NULL, "opt is NULL");
+  if (chunk_dtype != TAW_F32 && chunk_dtype != TAW_BF16) return fail(TAW_ERR_DTYPE, "chunk_dtype %d is neither TAW_F32 nor TAW_BF16", chunk_dtype);
+  if (opt->step < 1) return fail(TAW_ERR_SHAPE, "step=%d must be >= 1", opt->step);
+  if (!(opt->beta1 >= 0.f && opt->beta1 < 1.f) || !(opt->beta2 >= 0.f && opt->beta2 < 1.f) || !(opt->eps >= 0.f))
+    return fail(TAW_ERR_SHAPE, "need 0 <= beta1, beta2 < 1 and eps >= 0");
+  if (n_elems == 0) return TAW_OK;
+  TAW_REQUIRE_PTR(W_chunk); TAW_REQUIRE_PTR(master); TAW_REQUIRE_PTR(m); TAW_REQUIRE_PTR(v); TAW_REQUIRE_PTR(G_shard);
+  TAW_REQUIRE_ALIGNED(W_chunk); TAW_REQUIRE_ALIGNED(master); TAW_REQUIRE_ALIGNED(m); TAW_REQUIRE_ALIGNED(v); TAW_REQUIRE_ALIGNED(G_shard);
+  const char* ptrs[5] = {static_cast<const char*>(W_chunk), reinterpret_cast<const char*>(master), reinterpret_cast<const char*>(m),
+                         reinterpret_cast<const char*>(v), reinterpret_cast<const char*>(G_shard)};
+  const size_t lens[5] = {n_elems * dt_size(chunk_dtype), n_elems * 4, n_elems * 4, n_elems * 4, n_elems * 4};
+  for (int a = 0; a < 5; ++a)
+    for (int b = a + 1; b < 5; ++b)
+      if (ptrs[a] < ptrs[b] + lens[b] && ptrs[b] < ptrs[a] + lens[a]) return fail(TAW_ERR_SHAPE, "optimizer arrays overlap");
+  const double b1c = 1.0 - pow((double)opt->beta1, (double)opt->step), b2c = 1.0 - pow((double)opt->beta2, (double)opt->step);
+  TAW_LAUNCH(launch_adamw(chunk_dtype, W_chunk, master, m, v, G_shard, n_elems, opt->lr, opt->beta1, opt->beta2, opt->eps, opt->weight_decay,
+                          (float)b1c, (float)b2c, opt->grad_scale, opt->zero_grad, (hipStream_t)stream), "adamw kernel");
   return TAW_OK;
 }
 

@@ -34,6 +34,9 @@ int launch_swiglu_bwd(int dtype, int64_t T, int I, const void* da, const void* g
                       hipStream_t st);
 int launch_grad_accum(float* G, const void* g, int src_dtype, size_t n, float scale, hipStream_t st);
 int launch_stage_copy(void* dst, const void* src, size_t bytes, hipStream_t st);
+// AdamW over n elements; chunk in w_dtype, everything else fp32; b1c = 1 - beta1^t, b2c = 1 - beta2^t
+int launch_adamw(int w_dtype, void* chunk, float* master, float* m, float* v, float* G, size_t n, float lr, float beta1, float beta2,
+                 float eps, float wd, float b1c, float b2c, float gscale, int zero_grad, hipStream_t st);
 // D[b, h, t] = sum_i do[t, h*d + i] * o[t, h*d + i]   (o, do are [B*S, ld_o] / [B*S, ld_do])
 int launch_attn_rowdot(int dtype, int B, int S, int nh, int d, const void* o, int64_t ld_o,
                        const void* dO, int64_t ld_do, float* D, hipStream_t st);

@@ -31,7 +31,7 @@ def declared_functions():
 
 def test_every_declared_symbol_is_exported(lib):
     names = declared_functions()
-    assert len(names) == 20
+    assert len(names) == 21
     for n in names:
         assert hasattr(lib, n), f"{n} declared in include/ but not exported"
     assert set(names) == set(taw.EXPORTS)
@@ -151,6 +151,20 @@ def test_grad_accum_and_stage_validation(lib):
     with pytest.raises(taw.TawError) as e:
         taw.taw_weight_stage(ok, ok + 16, 32)
     assert e.value.status == taw.TAW_ERR_SHAPE           # overlap
+
+
+def test_optimizer_step_validation(lib):
+    ok = 0x10000
+    with pytest.raises(taw.TawError) as e:
+        taw.taw_optimizer_step(ok, 1, ok + 4096, ok + 8192, ok + 12288, ok + 16384, 16, 0)
+    assert e.value.status == taw.TAW_ERR_SHAPE            # steps are 1-based
+    with pytest.raises(taw.TawError) as e:
+        taw.taw_optimizer_step(ok, 1, ok + 16, ok + 8192, ok + 12288, ok + 16384, 16, 1)
+    assert e.value.status == taw.TAW_ERR_SHAPE            # chunk and master overlap
+    with pytest.raises(taw.TawError) as e:
+        taw.taw_optimizer_step(ok, 5, ok + 4096, ok + 8192, ok + 12288, ok + 16384, 16, 1)
+    assert e.value.status == taw.TAW_ERR_DTYPE
+    taw.taw_optimizer_step(None, 1, None, None, None, None, 0, 1)     # n = 0: nothing to do, nothing touched
 
 
 def test_op_validation(lib):

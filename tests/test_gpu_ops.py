@@ -287,3 +287,32 @@ def test_attention_mfma(taw, B, S, nh):
 def test_attention_mfma_peaked_scores(taw):
     """Scores of order 10: the running maximum moves a lot between key tiles."""
     _attn_case(taw, I.BF16, 1, 700, 2, 128, taw.TAW_IMPL_MFMA, seed=9, scale=3.0)
+
+
+@pytest.mark.parametrize("dtype", [I.F32, I.BF16])
+@pytest.mark.parametrize("n", [1, 7, 4096, 1 << 20])
+def test_optimizer_step(taw, dtype, n):
+    """Three AdamW steps over a shard against the oracle: master weights, both moments, the chunk in its
+    storage type, and the zeroed gradient shard."""
+    import torch
+    rng = np.random.default_rng(n)
+    w = rng.standard_normal(n).astype(np.float32)
+    master = torch.from_numpy(w.copy()).cuda()
+    m = torch.zeros(n, dtype=torch.float32, device="cuda")
+    v = torch.zeros(n, dtype=torch.float32, device="cuda")
+    chunk = U.empty_dev((n,), dtype)
+    w64, m64, v64 = w.astype(np.float64), np.zeros(n), np.zeros(n)
+    hp = dict(lr=1e-2, beta1=0.9, beta2=0.95, eps=1e-6, weight_decay=0.1, grad_scale=0.25)
+    for t in range(1, 4):
+        g = rng.standard_normal(n).astype(np.float32)
+        G = torch.from_numpy(g.copy()).cuda()
+        taw.taw_optimizer_step(chunk, dtype, master, m, v, G, n, t, zero_grad=(t == 3), **hp)
+        w64, m64, v64 = O.adamw_step(w64, m64, v64, g.astype(np.float64), t, hp["lr"], hp["beta1"], hp["beta2"], hp["eps"],
+                                     hp["weight_decay"], hp["grad_scale"])
+        torch.cuda.synchronize()
+        assert torch.count_nonzero(G).item() == (0 if t == 3 else np.count_nonzero(g))
+    assert U.tensor_scale_err(U.from_dev(master), w64) < 1e-6
+    assert U.tensor_scale_err(U.from_dev(m), m64) < 1e-6 and U.tensor_scale_err(U.from_dev(v), v64) < 1e-6
+    assert U.tensor_scale_err(U.from_dev(chunk), w64) < (4e-3 if dtype == I.BF16 else 1e-6)
+    if dtype == I.BF16:   # the chunk is exactly the master weights rounded to bf16
+        assert np.array_equal(I.to_storage(master.cpu().numpy(), dtype), chunk.view(torch.int16).cpu().numpy().view(np.uint16))

@@ -438,3 +438,32 @@ def test_sampled_attention_matches_the_full_definition():
     np.testing.assert_allclose(dq_t, dq[0, t0:, 0], rtol=1e-11, atol=1e-13)
     np.testing.assert_allclose(dk_t, dk[0, t0:, 0], rtol=1e-11, atol=1e-13)
     np.testing.assert_allclose(dv_t, dv[0, t0:, 0], rtol=1e-11, atol=1e-13)
+
+
+def test_adamw_step_against_closed_forms_and_a_library_optimizer():
+    """adamw_step: the first step from zero state moves every weight by lr * g/(|g| + eps) (+ decay),
+    zero gradient with zero state only decays, and five steps agree with torch.optim.AdamW in fp64."""
+    import torch
+    rng = np.random.default_rng(11)
+    w0, g = rng.standard_normal(1000), rng.standard_normal(1000)
+    z = np.zeros_like(w0)
+    w1, m1, v1 = O.adamw_step(w0, z, z, g, 1, 1e-2, 0.9, 0.999, 1e-8, 0.0)
+    np.testing.assert_allclose(w1, w0 - 1e-2 * g / (np.abs(g) + 1e-8), rtol=1e-12)
+    np.testing.assert_allclose(m1, 0.1 * g, rtol=1e-12)
+    np.testing.assert_allclose(v1, 0.001 * g * g, rtol=1e-12)
+    w1, _, _ = O.adamw_step(w0, z, z, z, 1, 1e-2, 0.9, 0.999, 1e-8, 0.1)
+    np.testing.assert_allclose(w1, w0 * (1 - 1e-3), rtol=1e-12)
+    # grad_scale is the same as scaling the gradient
+    a = O.adamw_step(w0, z, z, g, 3, 1e-3, 0.9, 0.95, 1e-6, 0.01, grad_scale=0.25)
+    b = O.adamw_step(w0, z, z, 0.25 * g, 3, 1e-3, 0.9, 0.95, 1e-6, 0.01)
+    for x, y in zip(a, b):
+        np.testing.assert_allclose(x, y, rtol=1e-13)
+    p = torch.nn.Parameter(torch.from_numpy(w0.copy()))
+    opt = torch.optim.AdamW([p], lr=3e-3, betas=(0.9, 0.95), eps=1e-6, weight_decay=0.05)
+    w, m, v = w0.copy(), z.copy(), z.copy()
+    for t in range(1, 6):
+        gt = rng.standard_normal(1000)
+        p.grad = torch.from_numpy(gt.copy())
+        opt.step()
+        w, m, v = O.adamw_step(w, m, v, gt, t, 3e-3, 0.9, 0.95, 1e-6, 0.05)
+    np.testing.assert_allclose(w, p.detach().numpy(), rtol=1e-10, atol=1e-12)
