@@ -40,6 +40,12 @@ PEAK_HBM_GBS = 8000.0
 # (FETCH_SIZE, WRITE_SIZE; each scaled by what the counter reads for the staging copy kernel, a plain copy of
 # known size): profiles/gemm_C2_hbm_traffic.md.  Only measured for the workload named.
 GEMM_TRAFFIC_BYTES_PER_LAUNCH = {"C2": 1465.9e6}
+# the paper's throughput table (Experiments, Throughput and Memory Usage): micro-batch size per sequence length and
+# TawPipe's tokens per GPU per second on its own hardware
+PAPER_TABLE_B = {4096: 16, 8192: 8, 16384: 4}
+PAPER_TABLE_TAWPIPE = {(1024, 4096): 13629.2, (1024, 8192): 11738.2, (1024, 16384): 8913.7, (2048, 4096): 5040.0,
+                       (2048, 8192): 4636.6, (2048, 16384): 4175.7, (4096, 4096): 1567.7, (4096, 8192): 1511.5,
+                       (4096, 16384): 1377.6}
 
 
 def model_flops(cfg):
@@ -54,7 +60,9 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="C2", choices=["C2", "C3", "C4", "C5"])
+    ap.add_argument("--workload", default="C2",
+                    help="C2 (default), C3, C4, C5, or a shape of the paper's throughput table as P-<H>-<S> "
+                         "(H in 1024/2048/4096, S in 4096/8192/16384; micro-batch size as in that table)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-leg", action="store_true")
     ap.add_argument("--no-recompute-leg", action="store_true")
@@ -71,7 +79,22 @@ def main():
 
     taw.load()
     torch.cuda.set_device(0)
-    cfg = I.CONFIGS[args.workload]
+    sweep = None
+    if args.workload in I.CONFIGS and args.workload != "C1":
+        cfg = I.CONFIGS[args.workload]
+    else:
+        # the paper's throughput table: 48-layer LLaMA-style models, heads of 128, I = 8H/3 rounded up to 256
+        try:
+            _, h_, s_ = args.workload.split("-")
+            h_, s_ = int(h_), int(s_)
+            b_ = PAPER_TABLE_B[s_]
+            assert h_ % 128 == 0
+        except Exception:
+            print(f"bench.py: unknown workload {args.workload!r}", file=sys.stderr)
+            sys.exit(2)
+        cfg = I.LayerConfig(args.workload, I.BF16, b_, s_, h_, h_ // 128, 128, (8 * h_ // 3 + 255) // 256 * 256)
+        sweep = {"layers": 48, "paper_tawpipe_tokens_per_s_per_gpu": PAPER_TABLE_TAWPIPE.get((h_, s_)),
+                 "paper_setup": "24 x A800, NVLink + 10GbE, fp16, activation checkpointing (context, not the target)"}
     desc_acc = taw.desc_from_config(cfg, 0)   # bwd overwrites the local gradient buffer
     L = taw.taw_layer_weight_layout(desc_acc)
     P = L["total_elems"]
@@ -173,6 +196,11 @@ def main():
         ms_rc = (time.perf_counter() - t0) * 1e3 / n_rc
         recompute = {"ms_per_step": round(ms_rc, 4), "model_TFLOPs": round(flops / ms_rc / 1e9, 2),
                      "ctx_bytes_saved": int(taw.taw_layer_ctx_bytes(desc_acc))}
+
+    if sweep is not None and recompute is not None:
+        # what one GPU's compute alone allows for the paper's 48-layer model in its training mode
+        # (activation checkpointing): tokens of a micro-batch / (48 x this layer's checkpointed step)
+        sweep["tokens_per_s_per_gpu_compute_only"] = round(cfg.B * cfg.S / (48 * recompute["ms_per_step"] * 1e-3), 1)
 
     # ---- per-kernel leg: HIP events on the launch stream around each launch
     def ev_time(fn, reps=5):
@@ -289,7 +317,7 @@ def main():
         "config": {"workload": f"{cfg.name}: bf16 decoder layer fwd+bwd, B={cfg.B} S={cfg.S} H={cfg.H} heads={cfg.n_heads}x{cfg.head_dim} "
                                f"I={cfg.I}, + weight staging on a side stream + fp32 grad-shard accumulation",
                    "model_flops_per_step": flops, "frac_of_bf16_mfma_peak": round(value / PEAK_BF16_TFLOPS, 4)},
-        "roofline": roofline, "cpu_baseline": cpu, "kernels": kernels, "overlap": overlap, "recompute": recompute,
+        "roofline": roofline, "cpu_baseline": cpu, "kernels": kernels, "overlap": overlap, "recompute": recompute, "paper_sweep": sweep,
     }
     print(json.dumps(out))
 
