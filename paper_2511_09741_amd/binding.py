@@ -38,6 +38,10 @@ class taw_adamw_desc(C.Structure):
                 ("weight_decay", C.c_float), ("grad_scale", C.c_float), ("step", C.c_int32), ("zero_grad", C.c_int32)]
 
 
+class taw_sched_desc(C.Structure):
+    _fields_ = [("P", C.c_int32), ("D", C.c_int32), ("L", C.c_int32), ("N", C.c_int32)]
+
+
 class TawError(RuntimeError):
     def __init__(self, status: int, name: str, detail: str):
         super().__init__(f"{name} ({status}): {detail}")
@@ -58,6 +62,11 @@ _SIGS = {
     "taw_grad_accum": (C.c_int, [_vp, _vp, _i32, _sz, _f, _vp]),
     "taw_weight_stage": (C.c_int, [_vp, _vp, _sz, _vp, _vp, _vp]),
     "taw_optimizer_step": (C.c_int, [C.POINTER(taw_adamw_desc), _vp, _i32, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "taw_sched_owner": (C.c_int, [C.POINTER(taw_sched_desc), _i32, C.POINTER(_i32), C.POINTER(_i32)]),
+    "taw_sched_step": (C.c_int, [C.POINTER(taw_sched_desc), _i32, _i32] + [C.POINTER(_i32)] * 4),
+    "taw_sched_update_step": (C.c_int, [C.POINTER(taw_sched_desc), _i32, C.POINTER(_i32)]),
+    "taw_sched_bubble_ratio": (C.c_int, [C.POINTER(taw_sched_desc), C.POINTER(C.c_double), C.POINTER(C.c_double)]),
+    "taw_sched_comm_elems": (C.c_int, [_i32, _i32, _i32, _i32] + [C.POINTER(C.c_double)] * 3),
     "taw_status_string": (C.c_char_p, [C.c_int]),
     "taw_last_error": (C.c_char_p, []),
     "taw_op_gemm": (C.c_int, [_i32, _i32, _i64, _i64, _i64, _vp, _i64, _vp, _i64, _vp, _i64, _i32, _i32, _vp, _i64, _i32, _vp]),
@@ -154,6 +163,45 @@ def taw_layer_bwd(desc, W_chunk, rope_table, x, dy, ctx, dx, G_shard, workspace,
         workspace_bytes = workspace.numel() * workspace.element_size()
     _check(load().taw_layer_bwd(C.byref(desc), _p(W_chunk), _p(rope_table), _p(x), _p(dy), _p(ctx), _p(dx), _p(G_shard),
                                 _p(workspace), workspace_bytes, _stream(stream)))
+
+
+# ---- schedule model (host only)
+def _sched_check(rc):
+    if rc != 0:
+        raise ValueError("taw_sched: invalid arguments")
+
+
+def taw_sched_owner(P, D, L, layer):
+    """(device, group) that owns `layer`."""
+    d, dev, grp = taw_sched_desc(P, D, L, 1), _i32(), _i32()
+    _sched_check(load().taw_sched_owner(C.byref(d), layer, C.byref(dev), C.byref(grp)))
+    return dev.value, grp.value
+
+
+def taw_sched_step(P, D, L, group, t):
+    """dict(phase, layer, master, prefetch_from) of `group` at step t."""
+    d = taw_sched_desc(P, D, L, 1)
+    ph, la, ma, pf = _i32(), _i32(), _i32(), _i32()
+    _sched_check(load().taw_sched_step(C.byref(d), group, t, C.byref(ph), C.byref(la), C.byref(ma), C.byref(pf)))
+    return {"phase": ph.value, "layer": la.value, "master": ma.value, "prefetch_from": pf.value}
+
+
+def taw_sched_update_step(P, D, L, layer):
+    d, t = taw_sched_desc(P, D, L, 1), _i32()
+    _sched_check(load().taw_sched_update_step(C.byref(d), layer, C.byref(t)))
+    return t.value
+
+
+def taw_sched_bubble_ratio(P, D, L, N):
+    d, a, b = taw_sched_desc(P, D, L, N), C.c_double(), C.c_double()
+    _sched_check(load().taw_sched_bubble_ratio(C.byref(d), C.byref(a), C.byref(b)))
+    return a.value, b.value
+
+
+def taw_sched_comm_elems(P, B, S, H):
+    a, b, c = C.c_double(), C.c_double(), C.c_double()
+    _sched_check(load().taw_sched_comm_elems(P, B, S, H, C.byref(a), C.byref(b), C.byref(c)))
+    return a.value, b.value, c.value
 
 
 def taw_optimizer_step(W_chunk, chunk_dtype, master, m, v, G_shard, n_elems, step, lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8,
