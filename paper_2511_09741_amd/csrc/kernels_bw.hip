@@ -49,27 +49,26 @@ __global__ void __launch_bounds__(256) rmsnorm_fwd_kernel(const T* __restrict__ 
 
 // =============================================================================== RMSNorm backward
 // c = dout*gamma;  dz = r c - z r^3 mean(c z) (+ dres);  dgamma_i = sum_t dout[t,i] z[t,i] r_t.
-// A wavefront walks rows with a grid stride and keeps its share of the dgamma column sums in
-// registers; the four wavefronts of a workgroup are then summed in a fixed order through LDS and
-// written as one partial row, which colsum_kernel reduces.  No atomics: results are reproducible.
+// A wavefront walks rows with a grid stride; a row's z and dout stay packed in registers between
+// the dot product and the write of dz.  The wavefront's share of the dgamma column sums lives in
+// its own LDS array (registers would not hold H/64 more floats per lane for wide rows), gamma is
+// read from LDS too.  The four arrays of a workgroup are then summed in a fixed order and written
+// as one partial row, which colsum_kernel reduces.  No atomics: results are reproducible.
 template <typename T, int V, int MAXC>
 __global__ void __launch_bounds__(256) rmsnorm_bwd_kernel(const T* __restrict__ dout, const T* __restrict__ z,
                                                           const float* __restrict__ r, const T* __restrict__ gamma,
                                                           const T* __restrict__ dres, T* __restrict__ dz,
                                                           float* __restrict__ partials, int64_t rows, int H) {
-  extern __shared__ float lds_cols[];  // [H]
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds_norm[];
+  float* lds_acc = reinterpret_cast<float*>(lds_norm);            // [4][H]
+  T* lds_g = reinterpret_cast<T*>(lds_acc + 4 * (size_t)H);       // [H]
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
   const int nch = H / V;
-  float acc[MAXC][V];
-  Vec<T, V> g[MAXC];
-#pragma unroll
-  for (int i = 0; i < MAXC; ++i) {
-    const int ci = i * 64 + lane;
-    if (ci < nch) g[i].load(gamma + ci * V);
-#pragma unroll
-    for (int j = 0; j < V; ++j) acc[i][j] = 0.f;
-  }
+  float* my_acc = lds_acc + (size_t)wave * H;
+  for (int c = threadIdx.x; c < H; c += 256) lds_g[c] = gamma[c];
+  for (int c = lane; c < H; c += 64) my_acc[c] = 0.f;
+  __syncthreads();
   const float invH = 1.0f / (float)H;
   for (int64_t row = (int64_t)blockIdx.x * 4 + wave; row < rows; row += (int64_t)gridDim.x * 4) {
     const int64_t base = row * (int64_t)H;
@@ -88,11 +87,14 @@ __global__ void __launch_bounds__(256) rmsnorm_bwd_kernel(const T* __restrict__ 
     for (int i = 0; i < MAXC; ++i) {
       const int ci = i * 64 + lane;
       if (ci < nch) {
+        Vec<T, V> g;
+        g.load(lds_g + ci * V);
+        float* ap = my_acc + ci * V;
 #pragma unroll
         for (int j = 0; j < V; ++j) {
           const float zz = zc[i].get(j), dd = dc[i].get(j);
-          dot += dd * g[i].get(j) * zz;
-          acc[i][j] += dd * zz * rr;
+          dot += dd * g.get(j) * zz;
+          ap[j] += dd * zz * rr;
         }
       }
     }
@@ -102,11 +104,12 @@ __global__ void __launch_bounds__(256) rmsnorm_bwd_kernel(const T* __restrict__ 
     for (int i = 0; i < MAXC; ++i) {
       const int ci = i * 64 + lane;
       if (ci < nch) {
-        Vec<T, V> o, res;
+        Vec<T, V> o, res, g;
+        g.load(lds_g + ci * V);
         if (dres) res.load(dres + base + ci * V);
 #pragma unroll
         for (int j = 0; j < V; ++j) {
-          float v = rr * dc[i].get(j) * g[i].get(j) - zc[i].get(j) * coef;
+          float v = rr * dc[i].get(j) * g.get(j) - zc[i].get(j) * coef;
           if (dres) v += res.get(j);
           o.set(j, v);
         }
@@ -114,25 +117,11 @@ __global__ void __launch_bounds__(256) rmsnorm_bwd_kernel(const T* __restrict__ 
       }
     }
   }
+  __syncthreads();
   // fixed-order sum of the four wavefronts' column sums
-  for (int w = 0; w < 4; ++w) {
-    if (wave == w) {
-#pragma unroll
-      for (int i = 0; i < MAXC; ++i) {
-        const int ci = i * 64 + lane;
-        if (ci < nch) {
-#pragma unroll
-          for (int j = 0; j < V; ++j) {
-            if (w == 0) lds_cols[ci * V + j] = acc[i][j];
-            else lds_cols[ci * V + j] += acc[i][j];
-          }
-        }
-      }
-    }
-    __syncthreads();
-  }
   float* prow = partials + (int64_t)blockIdx.x * H;
-  for (int c = threadIdx.x; c < H; c += 256) prow[c] = lds_cols[c];
+  for (int c = threadIdx.x; c < H; c += 256)
+    prow[c] = ((lds_acc[c] + lds_acc[(size_t)H + c]) + lds_acc[2 * (size_t)H + c]) + lds_acc[3 * (size_t)H + c];
 }
 
 // out[c] (=|+=) sum_p partials[p][c].  A workgroup owns 64 columns: thread (q = tid & 15, g = tid >> 4)
@@ -437,8 +426,13 @@ static int rmsnorm_bwd_dispatch(int64_t T_, int H, const T* dout, const T* z, co
   const int nch = H / V;
   int grid = (int)((T_ + 3) / 4);
   if (grid > kNormBwdGrid) grid = kNormBwdGrid;
-  const size_t lds = (size_t)H * sizeof(float);
-#define TAW_RN_BWD(MAXC) hipLaunchKernelGGL((rmsnorm_bwd_kernel<T, V, MAXC>), dim3(grid), dim3(256), lds, st, dout, z, r, g, dres, dz, partials, T_, H)
+  const size_t lds = 4 * (size_t)H * sizeof(float) + (size_t)H * sizeof(T);      // <= 144 KiB for the widest supported row
+#define TAW_RN_BWD(MAXC)                                                                                                     \
+  do {                                                                                                                     \
+    hipError_t e_ = hipFuncSetAttribute((const void*)rmsnorm_bwd_kernel<T, V, MAXC>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); \
+    if (e_ != hipSuccess) return (int)e_;                                                                                   \
+    hipLaunchKernelGGL((rmsnorm_bwd_kernel<T, V, MAXC>), dim3(grid), dim3(256), lds, st, dout, z, r, g, dres, dz, partials, T_, H); \
+  } while (0)
   if (nch <= 64) TAW_RN_BWD(1);
   else if (nch <= 128) TAW_RN_BWD(2);
   else if (nch <= 256) TAW_RN_BWD(4);
