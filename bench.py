@@ -7,8 +7,11 @@ One step = one pass of the whole hot path over one micro-batch of synthetic inpu
   taw_weight_stage   the other layer's weight chunk is copied owner-store -> staging buffer on a
                      side stream while this step computes (double buffered, two events)
   taw_layer_fwd      on the chunk staged during the previous step
-  taw_layer_bwd      weight gradients written into a local fp32 gradient buffer
-  taw_grad_accum     owner-side aggregation of that buffer into the fp32 gradient shard
+  taw_layer_bwd      weight gradients written into a local fp32 gradient buffer (two, used in turn)
+  taw_grad_accum     owner-side aggregation of that buffer into the fp32 gradient shard, on a second
+                     side stream: like the weights coming in, the gradients going out are off the
+                     compute stream (ready / consumed events per buffer), so the aggregation of step k
+                     runs beside the forward pass of step k+1
 Inputs are resident in HBM before the timed region.  The metric is model TFLOP/s of the layer's
 forward+backward: GEMMs 6 T H (4H+3I) + attention 12 B (S(S+1)/2) H (causal pairs, backward
 counted as 2x forward; the score recomputation inside the tiled backward is not credited).
@@ -19,7 +22,8 @@ Prints ONE JSON line.  Besides the contract fields it carries
                 launch stream, against the 2.5 PFLOP/s dense bf16 MFMA peak
   cpu_baseline  the fp64 CPU oracle timed on this machine's host cores on a bounded sample
   kernels       per-kernel-class rates measured the same way (attention, bandwidth kernels)
-  overlap       step time with and without the staging copy running beside it
+  overlap       step time with and without the staging copy running beside it, and with the
+                gradient aggregation on the compute stream instead of its side stream
   recompute     the same step in activation-checkpointing mode (TAW_RECOMPUTE): same model FLOPs
 """
 from __future__ import annotations
@@ -113,7 +117,8 @@ def main():
     del x_np, dy_np
     y, dx = torch.empty_like(x), torch.empty_like(x)
     stage_buf = [torch.empty_like(store[0]) for _ in range(2)]
-    g_local = torch.zeros(P, dtype=torch.float32, device="cuda")
+    g_locals = [torch.zeros(P, dtype=torch.float32, device="cuda") for _ in range(2)]
+    g_local = g_locals[0]
     G_shard = torch.zeros(P, dtype=torch.float32, device="cuda")
     ctx = torch.empty(taw.taw_layer_ctx_bytes(desc_acc), dtype=torch.uint8, device="cuda")
     desc_rc = taw.desc_from_config(cfg, taw.TAW_RECOMPUTE)      # activation checkpointing (extra leg below)
@@ -128,30 +133,42 @@ def main():
     ready = [torch.cuda.Event() for _ in range(2)]
     consumed = [torch.cuda.Event() for _ in range(2)]
     chunk_bytes = P * 2
+    agg_stream = torch.cuda.Stream()
+    g_ready = [torch.cuda.Event() for _ in range(2)]
+    g_consumed = [torch.cuda.Event() for _ in range(2)]
 
-    state = {"cur": 0, "layer": 0}
+    state = {"cur": 0, "layer": 0, "n": 0}
     taw.taw_weight_stage(stage_buf[0], store[0], chunk_bytes, copy_stream, None, ready[0])
     consumed[1].record(compute)
 
-    def step(staging=True):
+    def step(staging=True, agg_side=True):
         cur, nxt = state["cur"], state["cur"] ^ 1
+        gi = state["n"] & 1
+        state["n"] += 1
         if staging:
             taw.taw_weight_stage(stage_buf[nxt], store[(state["layer"] + 1) & 1], chunk_bytes, copy_stream,
                                  consumed[nxt], ready[nxt])
             compute.wait_event(ready[cur])
         taw.taw_layer_fwd(desc_acc, stage_buf[cur], rope, x, y, ctx, ws, ws_bytes, compute)
-        taw.taw_layer_bwd(desc_acc, stage_buf[cur], rope, x, dy, ctx, dx, g_local, ws, ws_bytes, compute)
+        compute.wait_event(g_consumed[gi])      # the aggregation of two steps ago has read this buffer
+        taw.taw_layer_bwd(desc_acc, stage_buf[cur], rope, x, dy, ctx, dx, g_locals[gi], ws, ws_bytes, compute)
         consumed[cur].record(compute)
-        taw.taw_grad_accum(G_shard, g_local, taw.TAW_F32, P, 1.0, compute)
+        if agg_side:
+            g_ready[gi].record(compute)
+            agg_stream.wait_event(g_ready[gi])
+            taw.taw_grad_accum(G_shard, g_locals[gi], taw.TAW_F32, P, 1.0, agg_stream)
+            g_consumed[gi].record(agg_stream)
+        else:
+            taw.taw_grad_accum(G_shard, g_locals[gi], taw.TAW_F32, P, 1.0, compute)
         if staging:
             state["cur"] = nxt
             state["layer"] += 1
 
-    def timed(nsteps, staging=True):
+    def timed(nsteps, staging=True, agg_side=True):
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for _ in range(nsteps):
-            step(staging)
+            step(staging, agg_side)
         torch.cuda.synchronize()
         return (time.perf_counter() - t0) * 1e3 / nsteps
 
@@ -169,6 +186,7 @@ def main():
     stage_buf[0].copy_(store[0]); stage_buf[1].copy_(store[1])
     ms_nostage = timed(max(3, args.steps // 2), staging=False)
     ms_stage = timed(max(3, args.steps // 2), staging=True)
+    ms_agg_serial = timed(max(3, args.steps // 2), staging=True, agg_side=False)
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     e0.record(copy_stream)
     taw.taw_weight_stage(stage_buf[state["cur"] ^ 1], store[0], chunk_bytes, copy_stream, None, None)
@@ -176,7 +194,8 @@ def main():
     torch.cuda.synchronize()
     copy_ms = e0.elapsed_time(e1)
     overlap = {"ms_per_step_staging": round(ms_stage, 4), "ms_per_step_no_staging": round(ms_nostage, 4),
-               "delta_frac": round(ms_stage / ms_nostage - 1.0, 4), "copy_alone_ms": round(copy_ms, 4),
+               "delta_frac": round(ms_stage / ms_nostage - 1.0, 4),
+               "ms_per_step_aggregation_on_compute_stream": round(ms_agg_serial, 4), "copy_alone_ms": round(copy_ms, 4),
                "copy_alone_GBs": round(2 * chunk_bytes / copy_ms / 1e6, 1)}
 
     # ---- activation-checkpointing mode: same model FLOPs, the backward re-runs the forward first
@@ -184,8 +203,14 @@ def main():
     if not args.no_recompute_leg:
         def step_rc():
             taw.taw_layer_fwd(desc_rc, stage_buf[0], rope, x, y, None, ws, ws_bytes_rc, compute)
-            taw.taw_layer_bwd(desc_rc, stage_buf[0], rope, x, dy, None, dx, g_local, ws, ws_bytes_rc, compute)
-            taw.taw_grad_accum(G_shard, g_local, taw.TAW_F32, P, 1.0, compute)
+            gi = state["n"] & 1
+            state["n"] += 1
+            compute.wait_event(g_consumed[gi])
+            taw.taw_layer_bwd(desc_rc, stage_buf[0], rope, x, dy, None, dx, g_locals[gi], ws, ws_bytes_rc, compute)
+            g_ready[gi].record(compute)
+            agg_stream.wait_event(g_ready[gi])
+            taw.taw_grad_accum(G_shard, g_locals[gi], taw.TAW_F32, P, 1.0, agg_stream)
+            g_consumed[gi].record(agg_stream)
         step_rc()
         torch.cuda.synchronize()
         t0 = time.perf_counter()
@@ -315,7 +340,7 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{cfg.name}: bf16 decoder layer fwd+bwd, B={cfg.B} S={cfg.S} H={cfg.H} heads={cfg.n_heads}x{cfg.head_dim} "
-                               f"I={cfg.I}, + weight staging on a side stream + fp32 grad-shard accumulation",
+                               f"I={cfg.I}, + weight staging and fp32 grad-shard aggregation on side streams",
                    "model_flops_per_step": flops, "frac_of_bf16_mfma_peak": round(value / PEAK_BF16_TFLOPS, 4)},
         "roofline": roofline, "cpu_baseline": cpu, "kernels": kernels, "overlap": overlap, "recompute": recompute, "paper_sweep": sweep,
     }

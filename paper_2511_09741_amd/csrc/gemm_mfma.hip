@@ -7,7 +7,10 @@
 // One 256-thread workgroup (4 wavefronts, one per SIMD) owns a 256x256 output tile; each
 // wavefront owns 128x128 of it as 4x4 MFMA tiles (256 fp32 accumulators per lane).  K advances in
 // steps of 64 through a double-buffered LDS tile pair (2 x 64 KiB), filled through registers so the
-// next step's global loads are in flight while the current step multiplies.
+// next step's global loads are in flight while the current step multiplies.  That is the general
+// kernel (any K % 8 == 0).  Two pipelined kernels with direct global->LDS loads take the shapes the
+// layer has: 64-deep steps for the NT and NN forms when K % 64 == 0, 32-deep steps for TN and for
+// K % 32 == 0 (namespace v2 below).
 //
 // LDS layouts.  A K-contiguous operand is stored [row][64] with its 16-byte chunks XOR-swizzled by
 // (row>>1)&7: every MFMA operand (8 consecutive k of one row) is one ds_read_b128 and 16
@@ -361,6 +364,108 @@ __device__ constexpr int kMfmaI[16] = {0, 0, 1, 1, 0, 1, 2, 2, 2, 0, 1, 2, 3, 3,
 __device__ constexpr int kMfmaJ[16] = {0, 1, 0, 1, 2, 2, 0, 1, 2, 3, 3, 3, 0, 1, 2, 3};
 __device__ constexpr int kReadOrder[8] = {0, 4, 5, 1, 6, 2, 7, 3};
 
+// ---- epilogue shared by the pipelined kernels: 32 x 128 accumulator blocks -> fp32 staging in LDS
+// ([32 rows][132] per wavefront, in the ring, which every wavefront has finished reading) ->
+// 16-byte accesses that cover whole row segments of C
+template <bool C_F32>
+__device__ __forceinline__ void store_tile(const f32x16_t (&acc)[4][4], unsigned char* lds2, int wave, int lane, int64_t m0, int64_t n0,
+                                           int wm, int wn, int64_t M, int64_t N, void* __restrict__ Cv, int64_t ldc, int accumulate,
+                                           const void* __restrict__ Rv, int64_t ldr) {
+  const int lcol = lane & 31, lrow = 4 * (lane >> 5);
+  if (C_F32) {
+    float* C = static_cast<float*>(Cv);
+    const float* R = static_cast<const float*>(Rv);
+    constexpr int SLD = 132;
+    float* stg = reinterpret_cast<float*>(lds2) + wave * (32 * SLD);
+    const bool vec_ok = (ldc & 3) == 0 && (!R || (ldr & 3) == 0);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) stg[(8 * (r >> 2) + lrow + (r & 3)) * SLD + 32 * j + lcol] = acc[i][j][r];
+      __builtin_amdgcn_s_waitcnt(0xc07f);
+      __builtin_amdgcn_wave_barrier();
+      // 32 rows x 128 cols = 1024 chunks of 4 columns; lane -> (row = idx >> 5, chunk = idx & 31): half a
+      // wavefront covers 512 contiguous bytes of a row
+#pragma unroll
+      for (int it = 0; it < 16; ++it) {
+        const int idx = it * 64 + lane, rr = idx >> 5, ch = idx & 31;
+        const int64_t row = m0 + wm + 32 * i + rr, col = n0 + wn + ch * 4;
+        if (row < M && col < N) {
+          f32x4_t v = *reinterpret_cast<const f32x4_t*>(stg + rr * SLD + ch * 4);
+          float* cp = C + row * ldc + col;
+          if (col + 4 <= N && vec_ok) {
+            if (R) v += *reinterpret_cast<const f32x4_t*>(R + row * ldr + col);
+            if (accumulate) v += *reinterpret_cast<const f32x4_t*>(cp);
+            *reinterpret_cast<f32x4_t*>(cp) = v;
+          } else {
+            for (int e = 0; e < 4 && col + e < N; ++e) {
+              float x = v[e];
+              if (R) x += R[row * ldr + col + e];
+              if (accumulate) x += cp[e];
+              cp[e] = x;
+            }
+          }
+        }
+      }
+      __builtin_amdgcn_s_waitcnt(0xc07f);
+      __builtin_amdgcn_wave_barrier();
+    }
+  } else {
+    // fp32 staging in LDS ([32 rows][132] per wavefront), then 16-byte coalesced bf16 rows
+    bf16_t* C = static_cast<bf16_t*>(Cv);
+    const bf16_t* R = static_cast<const bf16_t*>(Rv);
+    constexpr int SLD = 132;
+    float* stg = reinterpret_cast<float*>(lds2) + wave * (32 * SLD);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) stg[(8 * (r >> 2) + lrow + (r & 3)) * SLD + 32 * j + lcol] = acc[i][j][r];
+      __builtin_amdgcn_s_waitcnt(0xc07f);
+      __builtin_amdgcn_wave_barrier();
+      // 32 rows x 128 cols = 512 chunks of 8 columns; lane -> (row = idx >> 4, chunk = idx & 15)
+#pragma unroll
+      for (int it = 0; it < 8; ++it) {
+        const int idx = it * 64 + lane, rr = idx >> 4, ch = idx & 15;
+        const int64_t row = m0 + wm + 32 * i + rr, col = n0 + wn + ch * 8;
+        if (row < M && col < N) {
+          const f32x4_t v0 = *reinterpret_cast<const f32x4_t*>(stg + rr * SLD + ch * 8);
+          const f32x4_t v1 = *reinterpret_cast<const f32x4_t*>(stg + rr * SLD + ch * 8 + 4);
+          float v[8] = {v0[0], v0[1], v0[2], v0[3], v1[0], v1[1], v1[2], v1[3]};
+          if (col + 8 <= N && (ldc & 7) == 0 && (!R || (ldr & 7) == 0)) {
+            if (R) {
+              const bf16x8_t rv = *reinterpret_cast<const bf16x8_t*>(R + row * ldr + col);
+#pragma unroll
+              for (int e = 0; e < 8; ++e) v[e] += (float)rv[e];
+            }
+            if (accumulate) {
+              const bf16x8_t cv = *reinterpret_cast<const bf16x8_t*>(C + row * ldc + col);
+#pragma unroll
+              for (int e = 0; e < 8; ++e) v[e] += (float)cv[e];
+            }
+            bf16x8_t o;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) o[e] = (bf16_t)v[e];
+            *reinterpret_cast<bf16x8_t*>(C + row * ldc + col) = o;
+          } else {
+            for (int e = 0; e < 8 && col + e < N; ++e) {
+              float x = v[e];
+              if (R) x += (float)R[row * ldr + col + e];
+              if (accumulate) x += (float)C[row * ldc + col + e];
+              C[row * ldc + col + e] = (bf16_t)x;
+            }
+          }
+        }
+      }
+      __builtin_amdgcn_s_waitcnt(0xc07f);
+      __builtin_amdgcn_wave_barrier();
+    }
+  }
+}
+
 template <int MODE, bool C_F32>
 __global__ void __launch_bounds__(kThreads, 1)
 gemm_dlds_kernel(int64_t M, int64_t N, int64_t K, const bf16_t* __restrict__ A, int64_t lda, const bf16_t* __restrict__ B,
@@ -471,101 +576,219 @@ gemm_dlds_kernel(int64_t M, int64_t N, int64_t K, const bf16_t* __restrict__ A, 
   for (; kt + 3 < nk; ++kt) step(kt, std::true_type{});
   for (; kt < nk; ++kt) step(kt, std::false_type{});
 
-  // ---- epilogue: 32 x 128 accumulator blocks -> fp32 staging in LDS ([32 rows][132] per wavefront)
-  // -> 16-byte accesses that cover whole row segments of C
-  const int lcol = lane & 31, lrow = 4 * (lane >> 5);
-  if (C_F32) {
-    float* C = static_cast<float*>(Cv);
-    const float* R = static_cast<const float*>(Rv);
-    constexpr int SLD = 132;
-    float* stg = reinterpret_cast<float*>(lds2) + wave * (32 * SLD);
-    const bool vec_ok = (ldc & 3) == 0 && (!R || (ldr & 3) == 0);
+  store_tile<C_F32>(acc, lds2, wave, lane, m0, n0, wm, wn, M, N, Cv, ldc, accumulate, Rv, ldr);
+}
+
+// =============================================================================== 64-deep K steps
+// The same pipeline with K advancing 64 at a time through a ring of two 64 KiB stages.  What it buys:
+// a K-contiguous operand row is 128 bytes per step, one full cache line fetched by 8 adjacent lanes,
+// instead of two 64-byte halves fetched in two different steps (the L2 serves either as one request,
+// and a layer's forward and input-gradient GEMMs were bound by that request rate).
+//
+// A step is four MFMA k-steps q0..q3 of 16 MFMAs.  Its workgroup barrier sits after q2, not at the
+// end: the fragments of k-step 3 are read during q2, so at that barrier the stage is no longer read
+// and the next stage (loaded during q3 of the previous step and q0 of this one) has landed.  q3 then
+// already reads the first fragments of the next stage and starts refilling the stage just finished.
+//   KC tile [256 rows][64 k] (128-byte rows): load instruction j = 4 i + wave covers rows 8 j .. 8 j + 7;
+//      lane l writes slot (l & 7) of row 8 j + (l >> 3); slot s of row r holds chunk s ^ ((r >> 1) & 7)
+//      (16 consecutive rows of one chunk column then sit in 16 different bank groups).
+//   NC tile [64 k][256 cols]: as above with twice the k rows.
+constexpr int BK64 = 64;
+constexpr int kOp64 = 256 * BK64 * 2;            // one operand tile: 32 KiB
+constexpr int kStage64 = 2 * kOp64;              // 64 KiB
+constexpr size_t kLds64 = 2 * (size_t)kStage64;  // 128 KiB
+
+template <bool KC>
+struct Operand64 {
+  uint64_t base;          // tile origin at the current K position (bytes); wavefront-uniform
+  uint64_t kstep;         // bytes per K step
+  unsigned goff[8];       // per-lane byte offsets of the 8 loads of a step
+  // KC: rd[ks] for MFMA k-step ks, fragment i is 4096 i bytes further (32 rows)
+  // NC: rd[i] for fragment i; MFMA k-step ks adds 8192, the second transposing read of a fragment 2048
+  unsigned rd[4];
+
+  __device__ __forceinline__ void init(const bf16_t* mat, int64_t ld, int64_t origin, int64_t extent, int w0, int lane, int wave) {
+    if (KC) {
+      base = (uint64_t)(mat + origin * ld);
+      kstep = BK64 * 2;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-#pragma unroll
-      for (int j = 0; j < 4; ++j)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) stg[(8 * (r >> 2) + lrow + (r & 3)) * SLD + 32 * j + lcol] = acc[i][j][r];
-      __builtin_amdgcn_s_waitcnt(0xc07f);
-      __builtin_amdgcn_wave_barrier();
-      // 32 rows x 128 cols = 1024 chunks of 4 columns; lane -> (row = idx >> 5, chunk = idx & 31): half a
-      // wavefront covers 512 contiguous bytes of a row
-#pragma unroll
-      for (int it = 0; it < 16; ++it) {
-        const int idx = it * 64 + lane, rr = idx >> 5, ch = idx & 31;
-        const int64_t row = m0 + wm + 32 * i + rr, col = n0 + wn + ch * 4;
-        if (row < M && col < N) {
-          f32x4_t v = *reinterpret_cast<const f32x4_t*>(stg + rr * SLD + ch * 4);
-          float* cp = C + row * ldc + col;
-          if (col + 4 <= N && vec_ok) {
-            if (R) v += *reinterpret_cast<const f32x4_t*>(R + row * ldr + col);
-            if (accumulate) v += *reinterpret_cast<const f32x4_t*>(cp);
-            *reinterpret_cast<f32x4_t*>(cp) = v;
-          } else {
-            for (int e = 0; e < 4 && col + e < N; ++e) {
-              float x = v[e];
-              if (R) x += R[row * ldr + col + e];
-              if (accumulate) x += cp[e];
-              cp[e] = x;
-            }
-          }
-        }
+      for (int i = 0; i < 8; ++i) {
+        const int rt = 8 * (4 * i + wave) + (lane >> 3);      // row of the tile this lane's 16 bytes land in
+        int64_t r = rt;
+        if (origin + r >= extent) r = extent - 1 - origin;
+        const int c = (lane & 7) ^ ((rt >> 1) & 7);
+        goff[i] = (unsigned)(r * ld * 2 + c * 16);
       }
-      __builtin_amdgcn_s_waitcnt(0xc07f);
-      __builtin_amdgcn_wave_barrier();
-    }
-  } else {
-    // fp32 staging in LDS ([32 rows][132] per wavefront), then 16-byte coalesced bf16 rows
-    bf16_t* C = static_cast<bf16_t*>(Cv);
-    const bf16_t* R = static_cast<const bf16_t*>(Rv);
-    constexpr int SLD = 132;
-    float* stg = reinterpret_cast<float*>(lds2) + wave * (32 * SLD);
+      const int r = w0 + (lane & 31);
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+      for (int ks = 0; ks < 4; ++ks) rd[ks] = r * 128 + (((2 * ks + (lane >> 5)) ^ ((r >> 1) & 7)) << 4);
+    } else {
+      base = (uint64_t)(mat + origin);
+      kstep = (uint64_t)ld * (BK64 * 2);
 #pragma unroll
-      for (int j = 0; j < 4; ++j)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) stg[(8 * (r >> 2) + lrow + (r & 3)) * SLD + 32 * j + lcol] = acc[i][j][r];
-      __builtin_amdgcn_s_waitcnt(0xc07f);
-      __builtin_amdgcn_wave_barrier();
-      // 32 rows x 128 cols = 512 chunks of 8 columns; lane -> (row = idx >> 4, chunk = idx & 15)
-#pragma unroll
-      for (int it = 0; it < 8; ++it) {
-        const int idx = it * 64 + lane, rr = idx >> 4, ch = idx & 15;
-        const int64_t row = m0 + wm + 32 * i + rr, col = n0 + wn + ch * 8;
-        if (row < M && col < N) {
-          const f32x4_t v0 = *reinterpret_cast<const f32x4_t*>(stg + rr * SLD + ch * 8);
-          const f32x4_t v1 = *reinterpret_cast<const f32x4_t*>(stg + rr * SLD + ch * 8 + 4);
-          float v[8] = {v0[0], v0[1], v0[2], v0[3], v1[0], v1[1], v1[2], v1[3]};
-          if (col + 8 <= N && (ldc & 7) == 0 && (!R || (ldr & 7) == 0)) {
-            if (R) {
-              const bf16x8_t rv = *reinterpret_cast<const bf16x8_t*>(R + row * ldr + col);
-#pragma unroll
-              for (int e = 0; e < 8; ++e) v[e] += (float)rv[e];
-            }
-            if (accumulate) {
-              const bf16x8_t cv = *reinterpret_cast<const bf16x8_t*>(C + row * ldc + col);
-#pragma unroll
-              for (int e = 0; e < 8; ++e) v[e] += (float)cv[e];
-            }
-            bf16x8_t o;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) o[e] = (bf16_t)v[e];
-            *reinterpret_cast<bf16x8_t*>(C + row * ldc + col) = o;
-          } else {
-            for (int e = 0; e < 8 && col + e < N; ++e) {
-              float x = v[e];
-              if (R) x += (float)R[row * ldr + col + e];
-              if (accumulate) x += (float)C[row * ldc + col + e];
-              C[row * ldc + col + e] = (bf16_t)x;
-            }
-          }
-        }
+      for (int i = 0; i < 8; ++i) {
+        const int k = 2 * (4 * i + wave) + (lane >> 5);
+        int64_t col = ((lane & 31) ^ ((k & 3) << 2)) * 8;
+        if (origin + col >= extent) col = extent - 8 - origin;
+        goff[i] = (unsigned)((k * ld + col) * 2);
       }
-      __builtin_amdgcn_s_waitcnt(0xc07f);
-      __builtin_amdgcn_wave_barrier();
+      const int blk = lane >> 4, l16 = lane & 15;
+      const int k = 8 * (blk >> 1) + (l16 >> 2);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int n = w0 + 32 * i + 16 * (blk & 1) + 4 * (l16 & 3);
+        rd[i] = k * 512 + (((n >> 3) ^ ((k & 3) << 2)) << 4) + (n & 7) * 2;
+      }
     }
   }
+  __device__ __forceinline__ void dma(int i, unsigned lds_op, int wave) const { lds_dma16(base, goff[i], lds_op + (4 * i + wave) * 1024); }
+  __device__ __forceinline__ void advance() { base += kstep; }
+  __device__ __forceinline__ bf16x8_t frag(const lds_u8_t* op, int i, int ks) const {
+    if (KC) {
+      return *reinterpret_cast<const __attribute__((address_space(3))) bf16x8_t*>(op + rd[ks] + 4096 * i);
+    } else {
+      union { s16x4_t h[2]; bf16x8_t v; } u;
+#pragma unroll
+      for (int r = 0; r < 2; ++r)
+        u.h[r] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4_t __attribute__((address_space(3)))*)(op + rd[i] + 8192 * ks + 2048 * r));
+      return u.v;
+    }
+  }
+};
+
+template <int MODE, bool C_F32>
+__global__ void __launch_bounds__(kThreads, 1)
+gemm_dlds64_kernel(int64_t M, int64_t N, int64_t K, const bf16_t* __restrict__ A, int64_t lda, const bf16_t* __restrict__ B,
+                   int64_t ldb, void* __restrict__ Cv, int64_t ldc, int accumulate, const void* __restrict__ Rv, int64_t ldr,
+                   int tiles_m, int tiles_n) {
+  constexpr bool A_KC = (MODE != GEMM_TN);
+  constexpr bool B_KC = (MODE == GEMM_NT);
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds2[];
+  const lds_u8_t* lds = (const lds_u8_t*)lds2;
+  const unsigned lds0 = (unsigned)(size_t)lds;
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  // ---- XCD-aware tile id (see file header)
+  const int ntiles = tiles_m * tiles_n;
+  int pid = blockIdx.x;
+  const int n8 = ntiles & ~7;
+  if (pid < n8) pid = (pid & 7) * (n8 >> 3) + (pid >> 3);
+  constexpr int GROUP = 8;
+  const int per_group = GROUP * tiles_n;
+  const int g = pid / per_group;
+  const int gm0 = g * GROUP;
+  const int gsize = (tiles_m - gm0) < GROUP ? (tiles_m - gm0) : GROUP;
+  const int tm = gm0 + (pid % per_group) % gsize;
+  const int tn = (pid % per_group) / gsize;
+  const int64_t m0 = (int64_t)tm * BM, n0 = (int64_t)tn * BN;
+
+  const int wm = (wave >> 1) * 128, wn = (wave & 1) * 128;
+  Operand64<A_KC> oa;
+  Operand64<B_KC> ob;
+  oa.init(A, lda, m0, M, wm, lane, wave);
+  ob.init(B, ldb, n0, N, wn, lane, wave);
+
+  f32x16_t acc[4][4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  const int nk = (int)(K / BK64);
+  // ---- prologue: stage 0 whole and the A half of stage 1 in flight; stage 0 landed and visible
+#pragma unroll
+  for (int i = 0; i < 8; ++i) oa.dma(i, lds0, wave);
+#pragma unroll
+  for (int i = 0; i < 8; ++i) ob.dma(i, lds0 + kOp64, wave);
+  oa.advance();
+  ob.advance();
+  if (nk > 1) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) oa.dma(i, lds0 + kStage64, wave);
+    oa.advance();
+    wait_vmcnt<8>();
+  } else {
+    wait_vmcnt<0>();
+  }
+  stage_barrier();
+  __builtin_amdgcn_sched_barrier(0);
+
+  bf16x8_t fa[2][4], fb[2][4];     // [parity of the MFMA k-step][fragment]
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    fa[0][i] = oa.frag(lds, i, 0);
+    fb[0][i] = ob.frag(lds + kOp64, i, 0);
+  }
+  auto constexpr_mfma = [&](int e, int h) {
+    acc[kMfmaI[e]][kMfmaJ[e]] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[h][kMfmaI[e]], fb[h][kMfmaJ[e]], acc[kMfmaI[e]][kMfmaJ[e]], 0, 0, 0);
+  };
+  // one K step of 64.  LB: the B half of stage kt + 1 is still to be loaded (during q0); LA: stage
+  // kt + 2 exists, its A half is loaded during q3 into the stage this step has finished with;
+  // NEXT: stage kt + 1 exists, q3 reads its first fragments.
+  auto step = [&](int kt, auto lb_c, auto la_c, auto next_c) {
+    constexpr bool LB = decltype(lb_c)::value, LA = decltype(la_c)::value, NEXT = decltype(next_c)::value;
+    const lds_u8_t* cur = lds + (kt & 1) * kStage64;
+    const lds_u8_t* nxt = lds + ((kt + 1) & 1) * kStage64;
+    const unsigned dst_b = lds0 + ((kt + 1) & 1) * kStage64 + kOp64;
+    const unsigned dst_a = lds0 + (kt & 1) * kStage64;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int h = q & 1;
+      const lds_u8_t* src = q < 3 ? cur : nxt;
+      const int ks = (q + 1) & 3;
+      auto read = [&](int f) {
+        if (f < 4) fa[1 - h][f] = oa.frag(src, f, ks);
+        else fb[1 - h][f - 4] = ob.frag(src + kOp64, f - 4, ks);
+      };
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        constexpr_mfma(2 * e, h);
+        if (q == 2) {                    // all of k-step 3's fragments early: the barrier after q2 waits for them
+          if (e < 4) { read(kReadOrder[2 * e]); read(kReadOrder[2 * e + 1]); }
+        } else if (q < 3 || NEXT) {
+          read(kReadOrder[e]);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        constexpr_mfma(2 * e + 1, h);
+        if (LB && q == 0) ob.dma(e, dst_b, wave);
+        if (LA && q == 3) oa.dma(e, dst_a, wave);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      if (LB && q == 0) ob.advance();
+      if (LA && q == 3) oa.advance();
+      if (q == 2) {
+        __builtin_amdgcn_s_waitcnt(0xc07f);   // this wavefront's last reads of the stage have returned
+        wait_vmcnt<0>();                      // and its share of the next stage has landed
+        stage_barrier();
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+  };
+  __builtin_amdgcn_s_waitcnt(0xc07f);
+  int kt = 0;
+  for (; kt + 2 < nk; ++kt) step(kt, std::true_type{}, std::true_type{}, std::true_type{});
+  if (kt + 1 < nk) { step(kt, std::true_type{}, std::false_type{}, std::true_type{}); ++kt; }
+  step(kt, std::false_type{}, std::false_type{}, std::false_type{});
+
+  store_tile<C_F32>(acc, lds2, wave, lane, m0, n0, wm, wn, M, N, Cv, ldc, accumulate, Rv, ldr);
+}
+
+template <int MODE, bool C_F32>
+int launch_t64(int64_t M, int64_t N, int64_t K, const void* A, int64_t lda, const void* B, int64_t ldb, void* C, int64_t ldc,
+               int accumulate, const void* R, int64_t ldr, hipStream_t st) {
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute((const void*)gemm_dlds64_kernel<MODE, C_F32>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLds64);
+    if (e != hipSuccess) return (int)e;
+    attr_set = true;
+  }
+  const int tiles_m = (int)((M + BM - 1) / BM), tiles_n = (int)((N + BN - 1) / BN);
+  hipLaunchKernelGGL((gemm_dlds64_kernel<MODE, C_F32>), dim3((unsigned)(tiles_m * tiles_n)), dim3(kThreads), kLds64, st, M, N, K,
+                     (const bf16_t*)A, lda, (const bf16_t*)B, ldb, C, ldc, accumulate, R, ldr, tiles_m, tiles_n);
+  return (int)hipGetLastError();
 }
 
 template <int MODE, bool C_F32>
@@ -630,6 +853,14 @@ int launch_gemm_mfma(int mode, int64_t M, int64_t N, int64_t K, const void* A, i
       default: return f32 ? launch_t<GEMM_TN, true>(M, N, K, A, lda, B, ldb, C, ldc, accumulate, R, ldr, st)
                           : launch_t<GEMM_TN, false>(M, N, K, A, lda, B, ldb, C, ldc, accumulate, R, ldr, st);
     }
+  }
+  // K-contiguous operands gain from 64-deep steps (whole cache lines per row); the weight-gradient form has none
+  if (K % v2::BK64 == 0 && mode != GEMM_TN) {
+    if (mode == GEMM_NT)
+      return f32 ? v2::launch_t64<GEMM_NT, true>(M, N, K, A, lda, B, ldb, C, ldc, accumulate, R, ldr, st)
+                 : v2::launch_t64<GEMM_NT, false>(M, N, K, A, lda, B, ldb, C, ldc, accumulate, R, ldr, st);
+    return f32 ? v2::launch_t64<GEMM_NN, true>(M, N, K, A, lda, B, ldb, C, ldc, accumulate, R, ldr, st)
+               : v2::launch_t64<GEMM_NN, false>(M, N, K, A, lda, B, ldb, C, ldc, accumulate, R, ldr, st);
   }
   switch (mode) {
     case GEMM_NT: return f32 ? v2::launch_t2<GEMM_NT, true>(M, N, K, A, lda, B, ldb, C, ldc, accumulate, R, ldr, st)

@@ -247,10 +247,15 @@ def test_weight_stage_double_buffer(taw):
 
 
 # ----------------------------------------------------------------------------- MFMA kernels (bf16)
+# K % 64 == 0 runs the 64-deep pipelined kernel (1, 2, 3 and many K steps), K % 32 == 0 the 32-deep one,
+# any other K the register-staged kernel
 MFMA_GEMM_SHAPES = {
-    0: [(256, 256, 64), (8, 8, 8), (300, 520, 136), (257, 263, 72), (1000, 264, 4104), (512, 768, 1024), (1, 3, 8)],
-    1: [(256, 256, 64), (8, 8, 8), (300, 520, 136), (257, 264, 72), (1000, 264, 4104), (512, 768, 1024), (1, 8, 8)],
-    2: [(256, 256, 64), (8, 8, 8), (304, 520, 133), (264, 256, 77), (1000, 264, 4100), (512, 768, 1024), (8, 8, 1)],
+    0: [(256, 256, 64), (8, 8, 8), (300, 520, 136), (257, 263, 72), (1000, 264, 4104), (512, 768, 1024), (1, 3, 8),
+        (300, 520, 96), (257, 263, 128), (264, 520, 192), (300, 264, 160), (1000, 264, 4096), (5, 3, 32)],
+    1: [(256, 256, 64), (8, 8, 8), (300, 520, 136), (257, 264, 72), (1000, 264, 4104), (512, 768, 1024), (1, 8, 8),
+        (300, 520, 96), (257, 264, 128), (264, 520, 192), (300, 264, 160), (1000, 264, 4096), (5, 8, 32)],
+    2: [(256, 256, 64), (8, 8, 8), (304, 520, 133), (264, 256, 77), (1000, 264, 4100), (512, 768, 1024), (8, 8, 1),
+        (304, 520, 96), (264, 256, 128), (264, 520, 192), (304, 264, 160), (1000, 264, 4096), (8, 8, 32)],
 }
 
 
@@ -264,11 +269,11 @@ def test_gemm_mfma_shapes(taw, mode):
 
 @pytest.mark.parametrize("mode", [0, 1, 2])
 def test_gemm_mfma_epilogues(taw, mode):
-    shp = (520, 264, 200) if mode != 2 else (520, 264, 203)
-    _gemm_case(taw, I.BF16, mode, *shp, taw.TAW_IMPL_MFMA, residual=True)
-    _gemm_case(taw, I.BF16, mode, *shp, taw.TAW_IMPL_MFMA, c_f32=True)
-    _gemm_case(taw, I.BF16, mode, *shp, taw.TAW_IMPL_MFMA, c_f32=True, accumulate=True)
-    _gemm_case(taw, I.BF16, mode, *shp, taw.TAW_IMPL_MFMA, c_f32=True, accumulate=True, residual=True)
+    for shp in ((520, 264, 200) if mode != 2 else (520, 264, 203), (520, 264, 192), (520, 264, 160)):   # one per kernel
+        _gemm_case(taw, I.BF16, mode, *shp, taw.TAW_IMPL_MFMA, residual=True)
+        _gemm_case(taw, I.BF16, mode, *shp, taw.TAW_IMPL_MFMA, c_f32=True)
+        _gemm_case(taw, I.BF16, mode, *shp, taw.TAW_IMPL_MFMA, c_f32=True, accumulate=True)
+        _gemm_case(taw, I.BF16, mode, *shp, taw.TAW_IMPL_MFMA, c_f32=True, accumulate=True, residual=True)
 
 
 def test_gemm_mfma_fp32_output_is_accurate(taw):
