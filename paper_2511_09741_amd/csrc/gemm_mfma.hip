@@ -466,11 +466,29 @@ __device__ __forceinline__ void store_tile(const f32x16_t (&acc)[4][4], unsigned
   }
 }
 
+// one GEMM as the pipelined kernels take it
+struct GemmArgs {
+  int64_t M, N, K;
+  const bf16_t* A;
+  int64_t lda;
+  const bf16_t* B;
+  int64_t ldb;
+  void* C;
+  int64_t ldc;
+  int accumulate;
+  const void* R;
+  int64_t ldr;
+  int tiles_m, tiles_n;
+};
+
 template <int MODE, bool C_F32>
-__global__ void __launch_bounds__(kThreads, 1)
-gemm_dlds_kernel(int64_t M, int64_t N, int64_t K, const bf16_t* __restrict__ A, int64_t lda, const bf16_t* __restrict__ B,
-                 int64_t ldb, void* __restrict__ Cv, int64_t ldc, int accumulate, const void* __restrict__ Rv, int64_t ldr,
-                 int tiles_m, int tiles_n) {
+__device__ __forceinline__ void gemm_dlds_body(const GemmArgs& ga, int block) {
+  const int64_t M = ga.M, N = ga.N, K = ga.K, lda = ga.lda, ldb = ga.ldb, ldc = ga.ldc, ldr = ga.ldr;
+  const bf16_t* __restrict__ A = ga.A;
+  const bf16_t* __restrict__ B = ga.B;
+  void* __restrict__ Cv = ga.C;
+  const void* __restrict__ Rv = ga.R;
+  const int accumulate = ga.accumulate, tiles_m = ga.tiles_m, tiles_n = ga.tiles_n;
   constexpr bool A_KC = (MODE != GEMM_TN);
   constexpr bool B_KC = (MODE == GEMM_NT);
   extern __shared__ __attribute__((aligned(16))) unsigned char lds2[];
@@ -481,7 +499,7 @@ gemm_dlds_kernel(int64_t M, int64_t N, int64_t K, const bf16_t* __restrict__ A, 
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   // ---- XCD-aware tile id (see file header)
   const int ntiles = tiles_m * tiles_n;
-  int pid = blockIdx.x;
+  int pid = block;
   const int n8 = ntiles & ~7;
   if (pid < n8) pid = (pid & 7) * (n8 >> 3) + (pid >> 3);
   constexpr int GROUP = 8;
@@ -657,10 +675,13 @@ struct Operand64 {
 };
 
 template <int MODE, bool C_F32>
-__global__ void __launch_bounds__(kThreads, 1)
-gemm_dlds64_kernel(int64_t M, int64_t N, int64_t K, const bf16_t* __restrict__ A, int64_t lda, const bf16_t* __restrict__ B,
-                   int64_t ldb, void* __restrict__ Cv, int64_t ldc, int accumulate, const void* __restrict__ Rv, int64_t ldr,
-                   int tiles_m, int tiles_n) {
+__device__ __forceinline__ void gemm_dlds64_body(const GemmArgs& ga, int block) {
+  const int64_t M = ga.M, N = ga.N, K = ga.K, lda = ga.lda, ldb = ga.ldb, ldc = ga.ldc, ldr = ga.ldr;
+  const bf16_t* __restrict__ A = ga.A;
+  const bf16_t* __restrict__ B = ga.B;
+  void* __restrict__ Cv = ga.C;
+  const void* __restrict__ Rv = ga.R;
+  const int accumulate = ga.accumulate, tiles_m = ga.tiles_m, tiles_n = ga.tiles_n;
   constexpr bool A_KC = (MODE != GEMM_TN);
   constexpr bool B_KC = (MODE == GEMM_NT);
   extern __shared__ __attribute__((aligned(16))) unsigned char lds2[];
@@ -671,7 +692,7 @@ gemm_dlds64_kernel(int64_t M, int64_t N, int64_t K, const bf16_t* __restrict__ A
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   // ---- XCD-aware tile id (see file header)
   const int ntiles = tiles_m * tiles_n;
-  int pid = blockIdx.x;
+  int pid = block;
   const int n8 = ntiles & ~7;
   if (pid < n8) pid = (pid & 7) * (n8 >> 3) + (pid >> 3);
   constexpr int GROUP = 8;
@@ -776,33 +797,66 @@ gemm_dlds64_kernel(int64_t M, int64_t N, int64_t K, const bf16_t* __restrict__ A
   store_tile<C_F32>(acc, lds2, wave, lane, m0, n0, wm, wn, M, N, Cv, ldc, accumulate, Rv, ldr);
 }
 
-template <int MODE, bool C_F32>
-int launch_t64(int64_t M, int64_t N, int64_t K, const void* A, int64_t lda, const void* B, int64_t ldb, void* C, int64_t ldc,
-               int accumulate, const void* R, int64_t ldr, hipStream_t st) {
-  static bool attr_set = false;
+// ---- kernels: one GEMM, or two independent ones in one grid (the first's tiles, then the second's)
+template <int MODE, bool C_F32, bool K64>
+__global__ void __launch_bounds__(kThreads, 1) gemm_pipe_kernel(GemmArgs g) {
+  if (K64) gemm_dlds64_body<MODE, C_F32>(g, (int)blockIdx.x);
+  else gemm_dlds_body<MODE, C_F32>(g, (int)blockIdx.x);
+}
+// The layer's backward has such pairs at every linear: the input gradient and the weight gradient
+// read the same incoming gradient and write different outputs.  Neither tile count is a multiple
+// of the 256 compute units for every width, so two launches leave two partly filled last rounds;
+// one grid leaves one.  The weight-gradient tiles (longer: they contract over all tokens) go first.
+template <int MODE0, bool F32_0, bool K64_0, int MODE1, bool F32_1, bool K64_1>
+__global__ void __launch_bounds__(kThreads, 1) gemm_dual_kernel(GemmArgs g0, GemmArgs g1, int n0) {
+  if ((int)blockIdx.x < n0) {
+    if (K64_0) gemm_dlds64_body<MODE0, F32_0>(g0, (int)blockIdx.x);
+    else gemm_dlds_body<MODE0, F32_0>(g0, (int)blockIdx.x);
+  } else {
+    if (K64_1) gemm_dlds64_body<MODE1, F32_1>(g1, (int)blockIdx.x - n0);
+    else gemm_dlds_body<MODE1, F32_1>(g1, (int)blockIdx.x - n0);
+  }
+}
+
+inline GemmArgs make_args(int64_t M, int64_t N, int64_t K, const void* A, int64_t lda, const void* B, int64_t ldb, void* C, int64_t ldc,
+                          int accumulate, const void* R, int64_t ldr) {
+  GemmArgs g;
+  g.M = M; g.N = N; g.K = K;
+  g.A = (const bf16_t*)A; g.lda = lda;
+  g.B = (const bf16_t*)B; g.ldb = ldb;
+  g.C = C; g.ldc = ldc;
+  g.accumulate = accumulate;
+  g.R = R; g.ldr = ldr;
+  g.tiles_m = (int)((M + BM - 1) / BM);
+  g.tiles_n = (int)((N + BN - 1) / BN);
+  return g;
+}
+
+static_assert(kLds64 == kLds2, "the two pipelined kernels share one LDS size");
+
+template <int MODE, bool C_F32, bool K64>
+int launch_pipe(const GemmArgs& g, hipStream_t st) {
+  static bool attr_set = false;   // per instantiation; setting it again is harmless
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void*)gemm_dlds64_kernel<MODE, C_F32>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLds64);
+    hipError_t e = hipFuncSetAttribute((const void*)gemm_pipe_kernel<MODE, C_F32, K64>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLds2);
     if (e != hipSuccess) return (int)e;
     attr_set = true;
   }
-  const int tiles_m = (int)((M + BM - 1) / BM), tiles_n = (int)((N + BN - 1) / BN);
-  hipLaunchKernelGGL((gemm_dlds64_kernel<MODE, C_F32>), dim3((unsigned)(tiles_m * tiles_n)), dim3(kThreads), kLds64, st, M, N, K,
-                     (const bf16_t*)A, lda, (const bf16_t*)B, ldb, C, ldc, accumulate, R, ldr, tiles_m, tiles_n);
+  hipLaunchKernelGGL((gemm_pipe_kernel<MODE, C_F32, K64>), dim3((unsigned)(g.tiles_m * g.tiles_n)), dim3(kThreads), kLds2, st, g);
   return (int)hipGetLastError();
 }
 
-template <int MODE, bool C_F32>
-int launch_t2(int64_t M, int64_t N, int64_t K, const void* A, int64_t lda, const void* B, int64_t ldb, void* C, int64_t ldc,
-              int accumulate, const void* R, int64_t ldr, hipStream_t st) {
+template <int MODE0, bool F32_0, bool K64_0, int MODE1, bool F32_1, bool K64_1>
+int launch_dual(const GemmArgs& g0, const GemmArgs& g1, hipStream_t st) {
   static bool attr_set = false;
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void*)gemm_dlds_kernel<MODE, C_F32>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLds2);
+    hipError_t e = hipFuncSetAttribute((const void*)gemm_dual_kernel<MODE0, F32_0, K64_0, MODE1, F32_1, K64_1>,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLds2);
     if (e != hipSuccess) return (int)e;
     attr_set = true;
   }
-  const int tiles_m = (int)((M + BM - 1) / BM), tiles_n = (int)((N + BN - 1) / BN);
-  hipLaunchKernelGGL((gemm_dlds_kernel<MODE, C_F32>), dim3((unsigned)(tiles_m * tiles_n)), dim3(kThreads), kLds2, st, M, N, K,
-                     (const bf16_t*)A, lda, (const bf16_t*)B, ldb, C, ldc, accumulate, R, ldr, tiles_m, tiles_n);
+  const int n0 = g0.tiles_m * g0.tiles_n, n1 = g1.tiles_m * g1.tiles_n;
+  hipLaunchKernelGGL((gemm_dual_kernel<MODE0, F32_0, K64_0, MODE1, F32_1, K64_1>), dim3((unsigned)(n0 + n1)), dim3(kThreads), kLds2, st, g0, g1, n0);
   return (int)hipGetLastError();
 }
 
@@ -855,21 +909,29 @@ int launch_gemm_mfma(int mode, int64_t M, int64_t N, int64_t K, const void* A, i
     }
   }
   // K-contiguous operands gain from 64-deep steps (whole cache lines per row); the weight-gradient form has none
-  if (K % v2::BK64 == 0 && mode != GEMM_TN) {
-    if (mode == GEMM_NT)
-      return f32 ? v2::launch_t64<GEMM_NT, true>(M, N, K, A, lda, B, ldb, C, ldc, accumulate, R, ldr, st)
-                 : v2::launch_t64<GEMM_NT, false>(M, N, K, A, lda, B, ldb, C, ldc, accumulate, R, ldr, st);
-    return f32 ? v2::launch_t64<GEMM_NN, true>(M, N, K, A, lda, B, ldb, C, ldc, accumulate, R, ldr, st)
-               : v2::launch_t64<GEMM_NN, false>(M, N, K, A, lda, B, ldb, C, ldc, accumulate, R, ldr, st);
-  }
+  const v2::GemmArgs g = v2::make_args(M, N, K, A, lda, B, ldb, C, ldc, accumulate, R, ldr);
+  const bool k64 = K % v2::BK64 == 0 && mode != GEMM_TN;
   switch (mode) {
-    case GEMM_NT: return f32 ? v2::launch_t2<GEMM_NT, true>(M, N, K, A, lda, B, ldb, C, ldc, accumulate, R, ldr, st)
-                             : v2::launch_t2<GEMM_NT, false>(M, N, K, A, lda, B, ldb, C, ldc, accumulate, R, ldr, st);
-    case GEMM_NN: return f32 ? v2::launch_t2<GEMM_NN, true>(M, N, K, A, lda, B, ldb, C, ldc, accumulate, R, ldr, st)
-                             : v2::launch_t2<GEMM_NN, false>(M, N, K, A, lda, B, ldb, C, ldc, accumulate, R, ldr, st);
-    default: return f32 ? v2::launch_t2<GEMM_TN, true>(M, N, K, A, lda, B, ldb, C, ldc, accumulate, R, ldr, st)
-                        : v2::launch_t2<GEMM_TN, false>(M, N, K, A, lda, B, ldb, C, ldc, accumulate, R, ldr, st);
+    case GEMM_NT:
+      if (k64) return f32 ? v2::launch_pipe<GEMM_NT, true, true>(g, st) : v2::launch_pipe<GEMM_NT, false, true>(g, st);
+      return f32 ? v2::launch_pipe<GEMM_NT, true, false>(g, st) : v2::launch_pipe<GEMM_NT, false, false>(g, st);
+    case GEMM_NN:
+      if (k64) return f32 ? v2::launch_pipe<GEMM_NN, true, true>(g, st) : v2::launch_pipe<GEMM_NN, false, true>(g, st);
+      return f32 ? v2::launch_pipe<GEMM_NN, true, false>(g, st) : v2::launch_pipe<GEMM_NN, false, false>(g, st);
+    default:
+      return f32 ? v2::launch_pipe<GEMM_TN, true, false>(g, st) : v2::launch_pipe<GEMM_TN, false, false>(g, st);
   }
+}
+
+bool gemm_mfma_dual_supported(int64_t K_tn, int64_t K_nn) { return K_tn >= v2::BK2 && K_tn % v2::BK2 == 0 && K_nn >= v2::BK2 && K_nn % v2::BK2 == 0; }
+
+int launch_gemm_mfma_dual(int64_t M0, int64_t N0, int64_t K0, const void* A0, int64_t lda0, const void* B0, int64_t ldb0, float* C0,
+                          int64_t ldc0, int accumulate0, int64_t M1, int64_t N1, int64_t K1, const void* A1, int64_t lda1,
+                          const void* B1, int64_t ldb1, void* C1, int64_t ldc1, hipStream_t st) {
+  const v2::GemmArgs g0 = v2::make_args(M0, N0, K0, A0, lda0, B0, ldb0, C0, ldc0, accumulate0, nullptr, 0);
+  const v2::GemmArgs g1 = v2::make_args(M1, N1, K1, A1, lda1, B1, ldb1, C1, ldc1, 0, nullptr, 0);
+  if (K1 % v2::BK64 == 0) return v2::launch_dual<GEMM_TN, true, false, GEMM_NN, false, true>(g0, g1, st);
+  return v2::launch_dual<GEMM_TN, true, false, GEMM_NN, false, false>(g0, g1, st);
 }
 
 }  // namespace taw

@@ -162,6 +162,18 @@ static int gemm(const Plan& p, int dtype, int mode, int64_t M, int64_t N, int64_
   return launch_gemm_generic(dtype, mode, M, N, K, A, lda, B, ldb, C, ldc, c_dtype, accumulate, R, ldr, st);
 }
 
+// Backward of a linear y[T,N] = x[T,K] W[N,K]^T given dy: dx[T,K] = dy W (NN) and G[N,K] (+)= dy^T x (TN).
+// The two are independent; on the MFMA path they share one grid.
+static int linear_bwd(const Plan& p, int dtype, int64_t T, int64_t N, int64_t K, const void* dy, const void* W, const void* x,
+                      void* dx, float* G, int accumulate, hipStream_t st) {
+  if (p.mfma_gemm && gemm_mfma_supported(dtype, GEMM_NN, T, K, N, N, K, K, dtype, 0) &&
+      gemm_mfma_supported(dtype, GEMM_TN, N, K, T, N, K, K, DT_F32, 0) && gemm_mfma_dual_supported(T, N))
+    return launch_gemm_mfma_dual(N, K, T, dy, N, x, K, G, K, accumulate, T, K, N, dy, N, W, K, dx, K, st);
+  int rc = gemm(p, dtype, GEMM_NN, T, K, N, dy, N, W, K, dx, K, dtype, 0, nullptr, 0, st);
+  if (rc) return rc;
+  return gemm(p, dtype, GEMM_TN, N, K, T, dy, N, x, K, G, K, DT_F32, accumulate, nullptr, 0, st);
+}
+
 static const char* at(const void* base, size_t elem_off, int dtype) { return static_cast<const char*>(base) + elem_off * dt_size(dtype); }
 
 // ------------------------------------------------------------------------------ rope table
@@ -255,18 +267,15 @@ extern "C" int taw_layer_bwd(const taw_layer_desc* desc, const void* W_chunk, co
   }
 
   // y = h + a Wd^T :  da = dy Wd ;  G.Wd (+)= dy^T a
-  TAW_LAUNCH(gemm(p, dt, GEMM_NN, T, I, H, dy, H, at(W_chunk, L.w_down, dt), I, w.da, I, dt, 0, nullptr, 0, st), "gemm da");
-  TAW_LAUNCH(gemm(p, dt, GEMM_TN, H, I, T, dy, H, c.a, I, G_shard + L.w_down, I, DT_F32, acc, nullptr, 0, st), "gemm G.w_down");
+  TAW_LAUNCH(linear_bwd(p, dt, T, H, I, dy, at(W_chunk, L.w_down, dt), c.a, w.da, G_shard + L.w_down, acc, st), "gemm da, G.w_down");
   // a = silu(g) u
   TAW_LAUNCH(launch_swiglu_bwd(dt, T, (int)I, w.da, c.gu, w.dgu, st), "swiglu_bwd");
   // gu = hn Wgu^T :  dhn = dgu Wgu ;  G.Wgu (+)= dgu^T hn
-  TAW_LAUNCH(gemm(p, dt, GEMM_NN, T, H, 2 * I, w.dgu, 2 * I, at(W_chunk, L.w_gate_up, dt), H, w.dhn, H, dt, 0, nullptr, 0, st), "gemm dhn");
-  TAW_LAUNCH(gemm(p, dt, GEMM_TN, 2 * I, H, T, w.dgu, 2 * I, c.hn, H, G_shard + L.w_gate_up, H, DT_F32, acc, nullptr, 0, st), "gemm G.w_gate_up");
+  TAW_LAUNCH(linear_bwd(p, dt, T, 2 * I, H, w.dgu, at(W_chunk, L.w_gate_up, dt), c.hn, w.dhn, G_shard + L.w_gate_up, acc, st), "gemm dhn, G.w_gate_up");
   // hn = rmsnorm(h) :  dh = dy + rmsnorm_bwd(dhn) ;  G.gamma_mlp
   TAW_LAUNCH(launch_rmsnorm_bwd(dt, T, (int)H, w.dhn, c.h, c.r2, at(W_chunk, L.gamma_mlp, dt), dy, w.dh, G_shard + L.gamma_mlp, acc, w.partials, st), "rmsnorm_bwd(mlp)");
   // h = x + o Wo^T :  do = dh Wo ;  G.Wo (+)= dh^T o
-  TAW_LAUNCH(gemm(p, dt, GEMM_NN, T, H, H, w.dh, H, at(W_chunk, L.w_o, dt), H, w.dO, H, dt, 0, nullptr, 0, st), "gemm do");
-  TAW_LAUNCH(gemm(p, dt, GEMM_TN, H, H, T, w.dh, H, c.o, H, G_shard + L.w_o, H, DT_F32, acc, nullptr, 0, st), "gemm G.w_o");
+  TAW_LAUNCH(linear_bwd(p, dt, T, H, H, w.dh, at(W_chunk, L.w_o, dt), c.o, w.dO, G_shard + L.w_o, acc, st), "gemm do, G.w_o");
   // attention backward
   if (p.mfma_attn) {
     TAW_LAUNCH(launch_attn_bwd_mfma(desc->B, desc->S, desc->n_heads, c.qkv, c.o, w.dO, c.lse, w.D, w.dqkv, st), "attention bwd (mfma)");
@@ -277,8 +286,7 @@ extern "C" int taw_layer_bwd(const taw_layer_desc* desc, const void* W_chunk, co
   // rotary backward on dq, dk
   TAW_LAUNCH(launch_rope(dt, desc->B, desc->S, (int)(2 * H), desc->head_dim, w.dqkv, 3 * H, rope_table, 1, st), "rope bwd");
   // qkv = xn Wqkv^T :  dxn = dqkv Wqkv ;  G.Wqkv (+)= dqkv^T xn
-  TAW_LAUNCH(gemm(p, dt, GEMM_NN, T, H, 3 * H, w.dqkv, 3 * H, at(W_chunk, L.w_qkv, dt), H, w.dxn, H, dt, 0, nullptr, 0, st), "gemm dxn");
-  TAW_LAUNCH(gemm(p, dt, GEMM_TN, 3 * H, H, T, w.dqkv, 3 * H, c.xn, H, G_shard + L.w_qkv, H, DT_F32, acc, nullptr, 0, st), "gemm G.w_qkv");
+  TAW_LAUNCH(linear_bwd(p, dt, T, 3 * H, H, w.dqkv, at(W_chunk, L.w_qkv, dt), c.xn, w.dxn, G_shard + L.w_qkv, acc, st), "gemm dxn, G.w_qkv");
   // xn = rmsnorm(x) :  dx = dh + rmsnorm_bwd(dxn) ;  G.gamma_attn
   TAW_LAUNCH(launch_rmsnorm_bwd(dt, T, (int)H, w.dxn, x, c.r1, at(W_chunk, L.gamma_attn, dt), w.dh, dx, G_shard + L.gamma_attn, acc, w.partials, st), "rmsnorm_bwd(attn)");
   return TAW_OK;

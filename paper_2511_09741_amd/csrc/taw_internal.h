@@ -60,6 +60,12 @@ bool gemm_mfma_supported(int dtype, int mode, int64_t M, int64_t N, int64_t K, i
 int launch_gemm_mfma(int mode, int64_t M, int64_t N, int64_t K, const void* A, int64_t lda, const void* B,
                      int64_t ldb, void* C, int64_t ldc, int c_dtype, int accumulate, const void* R,
                      int64_t ldr, hipStream_t st);
+// A weight gradient C0[M0,N0] (fp32, TN form, optionally accumulated) and an input gradient C1[M1,N1] (bf16, NN form) in one
+// grid: the pair every linear of the backward has.  Needs both K % 32 == 0 on top of gemm_mfma_supported for each.
+bool gemm_mfma_dual_supported(int64_t K_tn, int64_t K_nn);
+int launch_gemm_mfma_dual(int64_t M0, int64_t N0, int64_t K0, const void* A0, int64_t lda0, const void* B0, int64_t ldb0, float* C0,
+                          int64_t ldc0, int accumulate0, int64_t M1, int64_t N1, int64_t K1, const void* A1, int64_t lda1,
+                          const void* B1, int64_t ldb1, void* C1, int64_t ldc1, hipStream_t st);
 // bf16, head_dim 128, and S * 3 * n_heads * head_dim * 2 bytes below 4 GiB (32-bit row offsets inside one batch element)
 bool attn_mfma_supported(int dtype, int S, int nh, int d);
 int launch_attn_fwd_mfma(int B, int S, int nh, const void* qkv, void* o, float* lse, hipStream_t st);
