@@ -364,6 +364,66 @@ __device__ constexpr int kMfmaI[16] = {0, 0, 1, 1, 0, 1, 2, 2, 2, 0, 1, 2, 3, 3,
 __device__ constexpr int kMfmaJ[16] = {0, 1, 0, 1, 2, 2, 0, 1, 2, 3, 3, 3, 0, 1, 2, 3};
 __device__ constexpr int kReadOrder[8] = {0, 4, 5, 1, 6, 2, 7, 3};
 
+// ---- the same for a tile that lies wholly inside C with 16-byte aligned row segments (all tiles of
+// the layer's shapes): no per-element checks, 32-bit lane offsets from the wavefront's corner of C
+template <bool C_F32>
+__device__ __forceinline__ void store_tile_full(const f32x16_t (&acc)[4][4], unsigned char* lds2, int wave, int lane, int64_t m0, int64_t n0,
+                                                int wm, int wn, void* __restrict__ Cv, int64_t ldc, int accumulate,
+                                                const void* __restrict__ Rv, int64_t ldr) {
+  constexpr int SLD = 132;
+  constexpr int ES = C_F32 ? 4 : 2;                       // bytes per element of C (and R)
+  float* stg = reinterpret_cast<float*>(lds2) + wave * (32 * SLD);
+  const int lcol = lane & 31, lrow = 4 * (lane >> 5);
+  char* cw = static_cast<char*>(Cv) + ((m0 + wm) * ldc + n0 + wn) * ES;
+  const char* rw = Rv ? static_cast<const char*>(Rv) + ((m0 + wm) * ldr + n0 + wn) * ES : nullptr;
+  // read-back: a lane takes 16 bytes of a row; C_F32: 32 lanes per row (2 rows per pass), else 16 lanes per row (4 rows per pass)
+  constexpr int LPR = C_F32 ? 32 : 16, RPP = 64 / LPR, NPASS = 32 / RPP;
+  const int rr0 = lane / LPR, ch = lane % LPR;
+  const unsigned coff0 = (unsigned)(rr0 * ldc) * ES + ch * 16, roff0 = (unsigned)(rr0 * ldr) * ES + ch * 16;
+  const unsigned cstep = (unsigned)(RPP * ldc) * ES, rstep = (unsigned)(RPP * ldr) * ES;
+  const float* srow = stg + rr0 * SLD + ch * (16 / ES);
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) stg[(8 * (r >> 2) + lrow + (r & 3)) * SLD + 32 * j + lcol] = acc[i][j][r];
+    __builtin_amdgcn_s_waitcnt(0xc07f);
+    __builtin_amdgcn_wave_barrier();
+    char* ci = cw + (int64_t)(32 * i) * ldc * ES;
+    const char* ri = rw ? rw + (int64_t)(32 * i) * ldr * ES : nullptr;
+#pragma unroll
+    for (int it = 0; it < NPASS; ++it) {
+      const float* sp = srow + it * RPP * SLD;
+      if (C_F32) {
+        f32x4_t v = *reinterpret_cast<const f32x4_t*>(sp);
+        if (ri) v += *reinterpret_cast<const f32x4_t*>(ri + roff0 + it * rstep);
+        if (accumulate) v += *reinterpret_cast<const f32x4_t*>(ci + coff0 + it * cstep);
+        *reinterpret_cast<f32x4_t*>(ci + coff0 + it * cstep) = v;
+      } else {
+        const f32x4_t v0 = *reinterpret_cast<const f32x4_t*>(sp), v1 = *reinterpret_cast<const f32x4_t*>(sp + 4);
+        float v[8] = {v0[0], v0[1], v0[2], v0[3], v1[0], v1[1], v1[2], v1[3]};
+        if (ri) {
+          const bf16x8_t rv = *reinterpret_cast<const bf16x8_t*>(ri + roff0 + it * rstep);
+#pragma unroll
+          for (int e = 0; e < 8; ++e) v[e] += (float)rv[e];
+        }
+        if (accumulate) {
+          const bf16x8_t cv = *reinterpret_cast<const bf16x8_t*>(ci + coff0 + it * cstep);
+#pragma unroll
+          for (int e = 0; e < 8; ++e) v[e] += (float)cv[e];
+        }
+        bf16x8_t o;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) o[e] = (bf16_t)v[e];
+        *reinterpret_cast<bf16x8_t*>(ci + coff0 + it * cstep) = o;
+      }
+    }
+    __builtin_amdgcn_s_waitcnt(0xc07f);
+    __builtin_amdgcn_wave_barrier();
+  }
+}
+
 // ---- epilogue shared by the pipelined kernels: 32 x 128 accumulator blocks -> fp32 staging in LDS
 // ([32 rows][132] per wavefront, in the ring, which every wavefront has finished reading) ->
 // 16-byte accesses that cover whole row segments of C
@@ -371,6 +431,14 @@ template <bool C_F32>
 __device__ __forceinline__ void store_tile(const f32x16_t (&acc)[4][4], unsigned char* lds2, int wave, int lane, int64_t m0, int64_t n0,
                                            int wm, int wn, int64_t M, int64_t N, void* __restrict__ Cv, int64_t ldc, int accumulate,
                                            const void* __restrict__ Rv, int64_t ldr) {
+  {
+    constexpr int V = C_F32 ? 3 : 7;                      // elements per 16 bytes, minus one
+    const bool full = m0 + BM <= M && n0 + BN <= N && (ldc & V) == 0 && (!Rv || (ldr & V) == 0);    // workgroup-uniform
+    if (full) {
+      store_tile_full<C_F32>(acc, lds2, wave, lane, m0, n0, wm, wn, Cv, ldc, accumulate, Rv, ldr);
+      return;
+    }
+  }
   const int lcol = lane & 31, lrow = 4 * (lane >> 5);
   if (C_F32) {
     float* C = static_cast<float*>(Cv);
