@@ -418,6 +418,29 @@ __device__ __forceinline__ void store_rows_T(const f32x16_t (&acc)[4], float mul
   __builtin_amdgcn_wave_barrier();
 }
 
+// Inverse rotary rotation of a wavefront's transposed accumulators X^T[128 d][32 rows] in place, for
+// the gradients of rotated q and k (the rotation's transpose is the rotation by the opposite
+// angle).  Lane = sequence position, registers (4g, 4g+1) and (4g+2, 4g+3) of a d block are the
+// rotated pairs; table [S][64][2] fp32 (cos, sin).  In registers and in fp32: no extra pass over
+// the gradients and one rounding instead of two.
+__device__ __forceinline__ void rope_inverse_T(f32x16_t (&acc)[4], const float* __restrict__ table, int pos, int limit, int lane) {
+  const int hh = lane >> 5;
+  if (pos >= limit) pos = limit - 1;                   // rows beyond the sequence are dropped by the store
+  const float* tb = table + (int64_t)pos * D;          // 64 pairs x 2 floats
+#pragma unroll
+  for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      const f32x4_t cs = *reinterpret_cast<const f32x4_t*>(tb + 2 * (dt * 16 + 4 * g + 2 * hh));
+#pragma unroll
+      for (int e = 0; e < 2; ++e) {
+        const float a = acc[dt][4 * g + 2 * e], bb = acc[dt][4 * g + 2 * e + 1], c = cs[2 * e], sn = cs[2 * e + 1];
+        acc[dt][4 * g + 2 * e] = a * c + bb * sn;
+        acc[dt][4 * g + 2 * e + 1] = bb * c - a * sn;
+      }
+    }
+}
+
 // =============================================================================== backward: row statistics
 // prep [2][B*nh][Sp] fp32, Sp = S rounded up to 64:  prep[0] = lse * log2(e) (what the exp2-domain
 // recomputation subtracts), +inf for rows S..Sp-1 so that their probabilities come out as exactly 0;
@@ -461,7 +484,8 @@ __global__ void __launch_bounds__(256) attn_bwd_prep_kernel(const bf16_t* __rest
 //   dV^T += dO^T P;   dK^T += Q^T dS  (scaled by 1/sqrt(d) at the end)
 __global__ void __launch_bounds__(kThreads8, 1)
 attn_bwd_dkv_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dO, const float* __restrict__ lse2,
-                    const float* __restrict__ Dsum, bf16_t* __restrict__ dqkv, int B, int S, int Sp, int nh, float scale) {
+                    const float* __restrict__ Dsum, bf16_t* __restrict__ dqkv, int B, int S, int Sp, int nh, float scale,
+                    const float* __restrict__ rope) {
   constexpr int BKVW = 256, BQ = 64, NS = 4;
   constexpr int kStage = 2 * kTileBytes + 2 * BQ * 4;   // Q tile | dO tile | lse[64] | D[64]
   extern __shared__ __attribute__((aligned(256))) unsigned char lds_raw[];
@@ -604,6 +628,11 @@ attn_bwd_dkv_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ d
   bf16_t* stage = reinterpret_cast<bf16_t*>(lds_raw) + wave * (32 * 136);
   bf16_t* dkout = dqkv + (int64_t)b * S * ld + H + (int64_t)h * D;
   bf16_t* dvout = dkout + H;
+  if (rope) {                                          // k was rotated: its gradient goes back through the rotation
+    int ln = lane;
+    asm volatile("" : "+v"(ln));                       // table addresses are made here, not kept in registers through the loop
+    rope_inverse_T(dk, rope, kv0w + (ln & 31), S, ln);
+  }
   store_rows_T(dk, scale, stage, dkout, ld, kv0w, S, lane);
   store_rows_T(dv, 1.0f, stage, dvout, ld, kv0w, S, lane);
 }
@@ -615,7 +644,8 @@ attn_bwd_dkv_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ d
 //   dQ^T += K^T dS^T  (scaled by 1/sqrt(d) at the end)
 __global__ void __launch_bounds__(kThreads8, 1)
 attn_bwd_dq_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dO, const float* __restrict__ lse2,
-                   const float* __restrict__ Dsum, bf16_t* __restrict__ dqkv, int B, int S, int Sp, int nh, float scale) {
+                   const float* __restrict__ Dsum, bf16_t* __restrict__ dqkv, int B, int S, int Sp, int nh, float scale,
+                   const float* __restrict__ rope) {
   constexpr int BQ = 256, WQ = 32, BKV = 64, NS = 4;
   constexpr int kStage = 2 * kTileBytes;   // K tile | V tile
   extern __shared__ __attribute__((aligned(256))) unsigned char lds_raw[];
@@ -723,6 +753,11 @@ attn_bwd_dq_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dO
 
   bf16_t* stage = reinterpret_cast<bf16_t*>(lds_raw) + wave * (32 * 136);
   bf16_t* dqout = dqkv + (int64_t)b * S * ld + (int64_t)h * D;
+  if (rope) {
+    int ln = lane;
+    asm volatile("" : "+v"(ln));                       // table addresses are made here, not kept in registers through the loop
+    rope_inverse_T(dq, rope, q0w + (ln & 31), S, ln);
+  }
   store_rows_T(dq, scale, stage, dqout, ld, q0w, S, lane);
 }
 
@@ -751,7 +786,7 @@ int launch_attn_fwd_mfma(int B, int S, int nh, const void* qkv, void* o, float* 
 size_t attn_bwd_mfma_scratch_floats(int B, int S, int nh) { return 2 * (size_t)B * nh * ((S + 63) / 64 * 64); }
 
 int launch_attn_bwd_mfma(int B, int S, int nh, const void* qkv, const void* o, const void* dO, const float* lse, float* prep,
-                         void* dqkv, hipStream_t st) {
+                         void* dqkv, const float* rope_table, hipStream_t st) {
   const float scale = 1.0f / sqrtf((float)D);
   const int Sp = (S + 63) / 64 * 64;
   const float* lse2 = prep;
@@ -770,7 +805,7 @@ int launch_attn_bwd_mfma(int B, int S, int nh, const void* qkv, const void* o, c
     if (e != hipSuccess) return (int)e;
     const int nkt = (S + 255) / 256;
     hipLaunchKernelGGL(attn_bwd_dkv_kernel, dim3((unsigned)(nkt * B * nh)), dim3(kThreads8), lds, st, (const bf16_t*)qkv, (const bf16_t*)dO, lse2, Dv,
-                       (bf16_t*)dqkv, B, S, Sp, nh, scale);
+                       (bf16_t*)dqkv, B, S, Sp, nh, scale, rope_table);
     int rc = (int)hipGetLastError();
     if (rc) return rc;
   }
@@ -780,7 +815,7 @@ int launch_attn_bwd_mfma(int B, int S, int nh, const void* qkv, const void* o, c
     if (e != hipSuccess) return (int)e;
     const int nqt = (S + 255) / 256;
     hipLaunchKernelGGL(attn_bwd_dq_kernel, dim3((unsigned)(nqt * B * nh)), dim3(kThreads8), lds, st, (const bf16_t*)qkv, (const bf16_t*)dO, lse2, Dv,
-                       (bf16_t*)dqkv, B, S, Sp, nh, scale);
+                       (bf16_t*)dqkv, B, S, Sp, nh, scale, rope_table);
     return (int)hipGetLastError();
   }
 }

@@ -277,14 +277,14 @@ extern "C" int taw_layer_bwd(const taw_layer_desc* desc, const void* W_chunk, co
   // h = x + o Wo^T :  do = dh Wo ;  G.Wo (+)= dh^T o
   TAW_LAUNCH(linear_bwd(p, dt, T, H, H, w.dh, at(W_chunk, L.w_o, dt), c.o, w.dO, G_shard + L.w_o, acc, st), "gemm do, G.w_o");
   // attention backward
+  // attention backward, then the rotary backward on dq, dk (the MFMA kernels apply it to their accumulators before storing)
   if (p.mfma_attn) {
-    TAW_LAUNCH(launch_attn_bwd_mfma(desc->B, desc->S, desc->n_heads, c.qkv, c.o, w.dO, c.lse, w.D, w.dqkv, st), "attention bwd (mfma)");
+    TAW_LAUNCH(launch_attn_bwd_mfma(desc->B, desc->S, desc->n_heads, c.qkv, c.o, w.dO, c.lse, w.D, w.dqkv, rope_table, st), "attention bwd (mfma)");
   } else {
     TAW_LAUNCH(launch_attn_rowdot(dt, desc->B, desc->S, desc->n_heads, desc->head_dim, c.o, H, w.dO, H, w.D, st), "attention row dot");
     TAW_LAUNCH(launch_attn_bwd_generic(dt, desc->B, desc->S, desc->n_heads, desc->head_dim, c.qkv, w.dO, c.lse, w.D, w.dqkv, st), "attention bwd (generic)");
+    TAW_LAUNCH(launch_rope(dt, desc->B, desc->S, (int)(2 * H), desc->head_dim, w.dqkv, 3 * H, rope_table, 1, st), "rope bwd");
   }
-  // rotary backward on dq, dk
-  TAW_LAUNCH(launch_rope(dt, desc->B, desc->S, (int)(2 * H), desc->head_dim, w.dqkv, 3 * H, rope_table, 1, st), "rope bwd");
   // qkv = xn Wqkv^T :  dxn = dqkv Wqkv ;  G.Wqkv (+)= dqkv^T xn
   TAW_LAUNCH(linear_bwd(p, dt, T, 3 * H, H, w.dqkv, at(W_chunk, L.w_qkv, dt), c.xn, w.dxn, G_shard + L.w_qkv, acc, st), "gemm dxn, G.w_qkv");
   // xn = rmsnorm(x) :  dx = dh + rmsnorm_bwd(dxn) ;  G.gamma_attn
@@ -481,7 +481,7 @@ extern "C" int taw_op_attn_bwd(int32_t dtype, int32_t B, int32_t S, int32_t n_he
   const hipStream_t st = (hipStream_t)stream;
   const int64_t H = (int64_t)n_heads * head_dim;
   if (mf) {
-    TAW_LAUNCH(launch_attn_bwd_mfma(B, S, n_heads, qkv, o, dO, lse, scratch, dqkv, st), "attention bwd (mfma)");
+    TAW_LAUNCH(launch_attn_bwd_mfma(B, S, n_heads, qkv, o, dO, lse, scratch, dqkv, nullptr, st), "attention bwd (mfma)");
   } else {
     TAW_LAUNCH(launch_attn_rowdot(dtype, B, S, n_heads, head_dim, o, H, dO, H, scratch, st), "attention row dot");
     TAW_LAUNCH(launch_attn_bwd_generic(dtype, B, S, n_heads, head_dim, qkv, dO, lse, scratch, dqkv, st), "attention bwd (generic)");

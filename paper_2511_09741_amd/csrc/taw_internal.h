@@ -71,8 +71,9 @@ bool attn_mfma_supported(int dtype, int S, int nh, int d);
 int launch_attn_fwd_mfma(int B, int S, int nh, const void* qkv, void* o, float* lse, hipStream_t st);
 // fp32 scratch of the MFMA backward: scaled lse and D, each padded to a multiple of 64 rows per (batch, head)
 size_t attn_bwd_mfma_scratch_floats(int B, int S, int nh);
-// computes its own row statistics (scratch) from o, dO and lse
+// computes its own row statistics (scratch) from o, dO and lse.  rope_table != nullptr: q and k were rotated
+// (table [S, 64, 2] fp32 of cos, sin) and dq, dk come out as gradients of the unrotated q, k
 int launch_attn_bwd_mfma(int B, int S, int nh, const void* qkv, const void* o, const void* dO, const float* lse,
-                         float* scratch, void* dqkv, hipStream_t st);
+                         float* scratch, void* dqkv, const float* rope_table, hipStream_t st);
 
 }  // namespace taw
