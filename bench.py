@@ -17,9 +17,9 @@ forward+backward: GEMMs 6 T H (4H+3I) + attention 12 B (S(S+1)/2) H (causal pair
 counted as 2x forward; the score recomputation inside the tiled backward is not credited).
 
 Prints ONE JSON line.  Besides the contract fields it carries
-  roofline      the dominant kernel (the bf16 MFMA GEMM, 12 launches per step): algorithmic FLOPs of
-                the 12 GEMMs / their summed launch durations, each measured with HIP events on the
-                launch stream, against the 2.5 PFLOP/s dense bf16 MFMA peak
+  roofline      the dominant kernel (the bf16 MFMA GEMM): algorithmic FLOPs of the step's 12 GEMM
+                shapes / their summed launch durations, each launched on its own and measured
+                with HIP events on the launch stream, against the 2.5 PFLOP/s dense bf16 MFMA peak
   cpu_baseline  the fp64 CPU oracle timed on this machine's host cores on a bounded sample
   kernels       per-kernel-class rates measured the same way (attention, bandwidth kernels)
   overlap       step time with and without the staging copy running beside it, and with the
@@ -43,7 +43,7 @@ PEAK_HBM_GBS = 8000.0
 # HBM-side bytes per GEMM launch (average of the 12 shapes of a step), from two rocprofv3 --pmc runs of this file
 # (FETCH_SIZE, WRITE_SIZE; each scaled by what the counter reads for the staging copy kernel, a plain copy of
 # known size): profiles/gemm_C2_hbm_traffic.md.  Only measured for the workload named.
-GEMM_TRAFFIC_BYTES_PER_LAUNCH = {"C2": 1465.9e6}
+GEMM_TRAFFIC_BYTES_PER_LAUNCH = {"C2": 1454.6e6}
 # the paper's throughput table (Experiments, Throughput and Memory Usage): micro-batch size per sequence length and
 # TawPipe's tokens per GPU per second on its own hardware
 PAPER_TABLE_B = {4096: 16, 8192: 8, 16384: 4}
@@ -271,7 +271,8 @@ def main():
             tot_fl += fl; tot_ms += t
             per[name] = {"ms": round(t, 4), "TFLOPs": round(fl / t / 1e9, 1)}
         achieved = tot_fl / tot_ms / 1e9
-        roofline = {"kernel": "gemm_mfma_kernel (bf16 MFMA GEMM, 12 launches per step)", "bound": "mfma",
+        roofline = {"kernel": "gemm_pipe_kernel (bf16 MFMA GEMM; the 12 GEMM shapes of a step, one launch each; inside "
+                              "taw_layer_bwd the 8 backward shapes run pairwise in one grid, gemm_dual_kernel)", "bound": "mfma",
                     "achieved": round(achieved, 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                     "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": GEMM_TRAFFIC_BYTES_PER_LAUNCH.get(args.workload),
                     "traffic_unit": "bytes per launch (L2 fills + write-backs, rocprofv3 FETCH_SIZE/WRITE_SIZE)",
