@@ -337,20 +337,26 @@ attn_fwd_kernel(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ o, float* _
 #pragma unroll
         for (int r = 0; r < 16; ++r) oacc[dt][r] *= alpha;
     }
+    // probabilities, packed to bf16 in pairs; the row sum is taken from the packed pairs (one dot
+    // product instruction per pair): the sum of exactly what the second product multiplies by
     float rs = 0.f;
+    const bf16x2_t ones = {(bf16_t)1.0f, (bf16_t)1.0f};
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const float p = fast_exp2(__builtin_fmaf(s[kb][r], c, -m));
-        s[kb][r] = p;
-        rs += p;
+      for (int t = 0; t < 2; ++t) {
+        u32x4_t w;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const float p0 = fast_exp2(__builtin_fmaf(s[kb][8 * t + 2 * j], c, -m));
+          const float p1 = fast_exp2(__builtin_fmaf(s[kb][8 * t + 2 * j + 1], c, -m));
+          const bf16x2_t pk = {(bf16_t)p0, (bf16_t)p1};
+          rs = __builtin_amdgcn_fdot2_f32_bf16(pk, ones, rs, false);
+          w[j] = __builtin_bit_cast(unsigned, pk);
+        }
+        pf[kb][t] = __builtin_bit_cast(bf16x8_t, w);
       }
     l += rs;
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-      for (int t = 0; t < 2; ++t) pf[kb][t] = pack8(s[kb], t);
     if (late) {
       pend = true;
       pend_tr = tr_t;
