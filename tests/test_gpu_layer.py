@@ -10,7 +10,7 @@ pytestmark = pytest.mark.gpu
 
 @pytest.mark.parametrize("seed", [0, 1, 2])
 def test_c1_fp32_tiny_layer(taw, seed):
-    """BASELINE config 1: fp32, B=1 S=128 H=64, 4 heads x 16, I=176; tensor-scale error <= 1e-4."""
+    """The smallest stated configuration: fp32, B=1 S=128 H=64, 4 heads x 16, I=176; tensor-scale error <= 1e-4."""
     U.check_layer(taw, I.CONFIGS["C1"], seed=seed)
 
 
