@@ -949,7 +949,7 @@ int launch_t(int64_t M, int64_t N, int64_t K, const void* A, int64_t lda, const 
 
 bool gemm_mfma_supported(int dtype, int mode, int64_t M, int64_t N, int64_t K, int64_t lda, int64_t ldb, int64_t ldc,
                          int c_dtype, int64_t ldr) {
-  (void)ldc; (void)ldr; (void)c_dtype;
+  (void)c_dtype;
   if (dtype != DT_BF16) return false;
   if (M <= 0 || N <= 0 || K <= 0) return false;
   if (lda % 8 || ldb % 8) return false;                     // 16-byte global loads
@@ -957,8 +957,8 @@ bool gemm_mfma_supported(int dtype, int mode, int64_t M, int64_t N, int64_t K, i
   else if (mode == GEMM_NN) { if (K % 8 || N % 8) return false; }
   else if (mode == GEMM_TN) { if (M % 8 || N % 8) return false; }
   else return false;
-  // per-thread offsets inside a tile are 32-bit
-  if (lda > ((int64_t)1 << 22) || ldb > ((int64_t)1 << 22)) return false;
+  // per-thread offsets inside a tile are 32-bit (operand loads, and the result / residual rows of the epilogue)
+  if (lda > ((int64_t)1 << 22) || ldb > ((int64_t)1 << 22) || ldc > ((int64_t)1 << 22) || ldr > ((int64_t)1 << 22)) return false;
   if ((M + BM - 1) / BM * ((N + BN - 1) / BN) > ((int64_t)1 << 30)) return false;
   return true;
 }
