@@ -366,10 +366,22 @@ __device__ constexpr int kReadOrder[8] = {0, 4, 5, 1, 6, 2, 7, 3};
 
 // ---- the same for a tile that lies wholly inside C with 16-byte aligned row segments (all tiles of
 // the layer's shapes): no per-element checks, 32-bit lane offsets from the wavefront's corner of C
-template <bool C_F32>
+//
+// EPI = kEpiRope (bf16 output only): the rotary embedding applied to the result before it is stored.
+// Columns below rot_cols are heads of 128 whose adjacent pairs (2i, 2i+1) are rotated by the angle of
+// (row % S, i); table [S][64][2] fp32 of (cos, sin).  A lane holds 8 consecutive columns of a row here,
+// i.e. 4 whole pairs, in fp32: the fused qkv projection then needs no rotary pass of its own, and q, k
+// are rounded to bf16 once.  rot_cols is a multiple of the tile width, so a tile rotates wholly or not.
+constexpr int kEpiNone = 0, kEpiRope = 1;
+struct EpiArgs {
+  const float* table;
+  int S;
+  int64_t rot_cols;
+};
+template <bool C_F32, int EPI = kEpiNone>
 __device__ __forceinline__ void store_tile_full(const f32x16_t (&acc)[4][4], unsigned char* lds2, int wave, int lane, int64_t m0, int64_t n0,
                                                 int wm, int wn, void* __restrict__ Cv, int64_t ldc, int accumulate,
-                                                const void* __restrict__ Rv, int64_t ldr) {
+                                                const void* __restrict__ Rv, int64_t ldr, EpiArgs ea = EpiArgs{nullptr, 1, 0}) {
   constexpr int SLD = 132;
   constexpr int ES = C_F32 ? 4 : 2;                       // bytes per element of C (and R)
   float* stg = reinterpret_cast<float*>(lds2) + wave * (32 * SLD);
@@ -392,6 +404,9 @@ __device__ __forceinline__ void store_tile_full(const f32x16_t (&acc)[4][4], uns
     __builtin_amdgcn_wave_barrier();
     char* ci = cw + (int64_t)(32 * i) * ldc * ES;
     const char* ri = rw ? rw + (int64_t)(32 * i) * ldr * ES : nullptr;
+    const bool rotate = EPI == kEpiRope && n0 < ea.rot_cols;                                   // workgroup-uniform
+    const int pos0 = EPI == kEpiRope ? (int)((m0 + wm + 32 * i + rr0) % ea.S) : 0;             // this lane's row in pass 0
+    const int pair0 = ((wn + ch * 8) & 127) >> 1;                                              // first of its 4 pairs inside the head
 #pragma unroll
     for (int it = 0; it < NPASS; ++it) {
       const float* sp = srow + it * RPP * SLD;
@@ -403,6 +418,21 @@ __device__ __forceinline__ void store_tile_full(const f32x16_t (&acc)[4][4], uns
       } else {
         const f32x4_t v0 = *reinterpret_cast<const f32x4_t*>(sp), v1 = *reinterpret_cast<const f32x4_t*>(sp + 4);
         float v[8] = {v0[0], v0[1], v0[2], v0[3], v1[0], v1[1], v1[2], v1[3]};
+        if constexpr (EPI == kEpiRope) {
+          if (rotate) {
+            int pos = pos0 + it * RPP;
+            pos = pos >= ea.S ? pos - ea.S : pos;      // rows of a pass-group never span more than one sequence boundary (S >= 32)
+            const float* tb = ea.table + ((int64_t)pos * 64 + pair0) * 2;
+            const f32x4_t cs0 = *reinterpret_cast<const f32x4_t*>(tb), cs1 = *reinterpret_cast<const f32x4_t*>(tb + 4);
+            const float cc[4] = {cs0[0], cs0[2], cs1[0], cs1[2]}, sn[4] = {cs0[1], cs0[3], cs1[1], cs1[3]};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              const float a = v[2 * e], b2 = v[2 * e + 1];
+              v[2 * e] = a * cc[e] - b2 * sn[e];
+              v[2 * e + 1] = a * sn[e] + b2 * cc[e];
+            }
+          }
+        }
         if (ri) {
           const bf16x8_t rv = *reinterpret_cast<const bf16x8_t*>(ri + roff0 + it * rstep);
 #pragma unroll
@@ -427,10 +457,14 @@ __device__ __forceinline__ void store_tile_full(const f32x16_t (&acc)[4][4], uns
 // ---- epilogue shared by the pipelined kernels: 32 x 128 accumulator blocks -> fp32 staging in LDS
 // ([32 rows][132] per wavefront, in the ring, which every wavefront has finished reading) ->
 // 16-byte accesses that cover whole row segments of C
-template <bool C_F32>
+template <bool C_F32, int EPI = kEpiNone>
 __device__ __forceinline__ void store_tile(const f32x16_t (&acc)[4][4], unsigned char* lds2, int wave, int lane, int64_t m0, int64_t n0,
                                            int wm, int wn, int64_t M, int64_t N, void* __restrict__ Cv, int64_t ldc, int accumulate,
-                                           const void* __restrict__ Rv, int64_t ldr) {
+                                           const void* __restrict__ Rv, int64_t ldr, EpiArgs ea = EpiArgs{nullptr, 1, 0}) {
+  if constexpr (EPI != kEpiNone) {      // the host only asks for a fused epilogue when every tile lies inside the matrix
+    store_tile_full<C_F32, EPI>(acc, lds2, wave, lane, m0, n0, wm, wn, Cv, ldc, accumulate, Rv, ldr, ea);
+    return;
+  }
   {
     constexpr int V = C_F32 ? 3 : 7;                      // elements per 16 bytes, minus one
     const bool full = m0 + BM <= M && n0 + BN <= N && (ldc & V) == 0 && (!Rv || (ldr & V) == 0);    // workgroup-uniform
@@ -547,6 +581,7 @@ struct GemmArgs {
   const void* R;
   int64_t ldr;
   int tiles_m, tiles_n;
+  EpiArgs epi;            // fused epilogues only
 };
 
 template <int MODE, bool C_F32>
@@ -742,7 +777,7 @@ struct Operand64 {
   }
 };
 
-template <int MODE, bool C_F32>
+template <int MODE, bool C_F32, int EPI = kEpiNone>
 __device__ __forceinline__ void gemm_dlds64_body(const GemmArgs& ga, int block) {
   const int64_t M = ga.M, N = ga.N, K = ga.K, lda = ga.lda, ldb = ga.ldb, ldc = ga.ldc, ldr = ga.ldr;
   const bf16_t* __restrict__ A = ga.A;
@@ -862,13 +897,14 @@ __device__ __forceinline__ void gemm_dlds64_body(const GemmArgs& ga, int block) 
   if (kt + 1 < nk) { step(kt, std::true_type{}, std::false_type{}, std::true_type{}); ++kt; }
   step(kt, std::false_type{}, std::false_type{}, std::false_type{});
 
-  store_tile<C_F32>(acc, lds2, wave, lane, m0, n0, wm, wn, M, N, Cv, ldc, accumulate, Rv, ldr);
+  store_tile<C_F32, EPI>(acc, lds2, wave, lane, m0, n0, wm, wn, M, N, Cv, ldc, accumulate, Rv, ldr, ga.epi);
 }
 
 // ---- kernels: one GEMM, or two independent ones in one grid (the first's tiles, then the second's)
-template <int MODE, bool C_F32, bool K64>
+template <int MODE, bool C_F32, bool K64, int EPI = kEpiNone>
 __global__ void __launch_bounds__(kThreads, 1) gemm_pipe_kernel(GemmArgs g) {
-  if (K64) gemm_dlds64_body<MODE, C_F32>(g, (int)blockIdx.x);
+  static_assert(EPI == kEpiNone || K64, "fused epilogues exist for the 64-deep loop only");
+  if constexpr (K64) gemm_dlds64_body<MODE, C_F32, EPI>(g, (int)blockIdx.x);
   else gemm_dlds_body<MODE, C_F32>(g, (int)blockIdx.x);
 }
 // The layer's backward has such pairs at every linear: the input gradient and the weight gradient
@@ -897,20 +933,21 @@ inline GemmArgs make_args(int64_t M, int64_t N, int64_t K, const void* A, int64_
   g.R = R; g.ldr = ldr;
   g.tiles_m = (int)((M + BM - 1) / BM);
   g.tiles_n = (int)((N + BN - 1) / BN);
+  g.epi = EpiArgs{nullptr, 1, 0};
   return g;
 }
 
 static_assert(kLds64 == kLds2, "the two pipelined kernels share one LDS size");
 
-template <int MODE, bool C_F32, bool K64>
+template <int MODE, bool C_F32, bool K64, int EPI = kEpiNone>
 int launch_pipe(const GemmArgs& g, hipStream_t st) {
   static bool attr_set = false;   // per instantiation; setting it again is harmless
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void*)gemm_pipe_kernel<MODE, C_F32, K64>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLds2);
+    hipError_t e = hipFuncSetAttribute((const void*)gemm_pipe_kernel<MODE, C_F32, K64, EPI>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLds2);
     if (e != hipSuccess) return (int)e;
     attr_set = true;
   }
-  hipLaunchKernelGGL((gemm_pipe_kernel<MODE, C_F32, K64>), dim3((unsigned)(g.tiles_m * g.tiles_n)), dim3(kThreads), kLds2, st, g);
+  hipLaunchKernelGGL((gemm_pipe_kernel<MODE, C_F32, K64, EPI>), dim3((unsigned)(g.tiles_m * g.tiles_n)), dim3(kThreads), kLds2, st, g);
   return (int)hipGetLastError();
 }
 
@@ -1000,6 +1037,17 @@ int launch_gemm_mfma_dual(int64_t M0, int64_t N0, int64_t K0, const void* A0, in
   const v2::GemmArgs g1 = v2::make_args(M1, N1, K1, A1, lda1, B1, ldb1, C1, ldc1, 0, nullptr, 0);
   if (K1 % v2::BK64 == 0) return v2::launch_dual<GEMM_TN, true, false, GEMM_NN, false, true>(g0, g1, st);
   return v2::launch_dual<GEMM_TN, true, false, GEMM_NN, false, false>(g0, g1, st);
+}
+
+bool gemm_mfma_rope_supported(int64_t M, int64_t N, int64_t K, int64_t rot_cols, int S) {
+  return M % BM == 0 && N % BN == 0 && K % v2::BK64 == 0 && rot_cols % BN == 0 && rot_cols % 128 == 0 && S >= 32;
+}
+
+int launch_gemm_mfma_nt_rope(int64_t M, int64_t N, int64_t K, const void* A, int64_t lda, const void* B, int64_t ldb, void* C, int64_t ldc,
+                             const float* rope_table, int S, int64_t rot_cols, hipStream_t st) {
+  v2::GemmArgs g = v2::make_args(M, N, K, A, lda, B, ldb, C, ldc, 0, nullptr, 0);
+  g.epi = v2::EpiArgs{rope_table, S, rot_cols};
+  return v2::launch_pipe<GEMM_NT, false, true, v2::kEpiRope>(g, st);
 }
 
 }  // namespace taw

@@ -195,10 +195,15 @@ static int run_fwd(const taw_layer_desc* desc, const Plan& p, const taw_weight_l
   const int64_t T = (int64_t)desc->B * desc->S, H = desc->H, I = desc->I;
   // xn = rmsnorm(x; gamma_attn)
   TAW_LAUNCH(launch_rmsnorm_fwd(dt, T, (int)H, x, at(W_chunk, L.gamma_attn, dt), desc->rms_eps, c.xn, c.r1, st), "rmsnorm_fwd(attn)");
-  // qkv = xn Wqkv^T
-  TAW_LAUNCH(gemm(p, dt, GEMM_NT, T, 3 * H, H, c.xn, H, at(W_chunk, L.w_qkv, dt), H, c.qkv, 3 * H, dt, 0, nullptr, 0, st), "gemm qkv");
-  // rotate q and k (the first 2H columns)
-  TAW_LAUNCH(launch_rope(dt, desc->B, desc->S, (int)(2 * H), desc->head_dim, c.qkv, 3 * H, rope_table, 0, st), "rope");
+  // qkv = xn Wqkv^T, q and k (the first 2H columns) rotated: in the GEMM's epilogue where its tiles allow it
+  if (p.mfma_gemm && dt == DT_BF16 && desc->head_dim == 128 && gemm_mfma_supported(dt, GEMM_NT, T, 3 * H, H, H, H, 3 * H, dt, 0) &&
+      gemm_mfma_rope_supported(T, 3 * H, H, 2 * H, desc->S)) {
+    TAW_LAUNCH(launch_gemm_mfma_nt_rope(T, 3 * H, H, c.xn, H, at(W_chunk, L.w_qkv, dt), H, c.qkv, 3 * H, rope_table, desc->S, 2 * H, st),
+               "gemm qkv + rope");
+  } else {
+    TAW_LAUNCH(gemm(p, dt, GEMM_NT, T, 3 * H, H, c.xn, H, at(W_chunk, L.w_qkv, dt), H, c.qkv, 3 * H, dt, 0, nullptr, 0, st), "gemm qkv");
+    TAW_LAUNCH(launch_rope(dt, desc->B, desc->S, (int)(2 * H), desc->head_dim, c.qkv, 3 * H, rope_table, 0, st), "rope");
+  }
   // o = causal softmax attention
   if (p.mfma_attn) TAW_LAUNCH(launch_attn_fwd_mfma(desc->B, desc->S, desc->n_heads, c.qkv, c.o, c.lse, st), "attention fwd (mfma)");
   else TAW_LAUNCH(launch_attn_fwd_generic(dt, desc->B, desc->S, desc->n_heads, desc->head_dim, c.qkv, c.o, c.lse, st), "attention fwd (generic)");

@@ -66,6 +66,12 @@ bool gemm_mfma_dual_supported(int64_t K_tn, int64_t K_nn);
 int launch_gemm_mfma_dual(int64_t M0, int64_t N0, int64_t K0, const void* A0, int64_t lda0, const void* B0, int64_t ldb0, float* C0,
                           int64_t ldc0, int accumulate0, int64_t M1, int64_t N1, int64_t K1, const void* A1, int64_t lda1,
                           const void* B1, int64_t ldb1, void* C1, int64_t ldc1, hipStream_t st);
+// C[M,N] = A[M,K] B[N,K]^T (bf16) with the rotary embedding applied in the epilogue to the columns below rot_cols (heads of
+// 128, adjacent pairs, row r at position r % S; table [S, 64, 2] fp32).  Needs M % 256 == 0, N % 256 == 0, K % 64 == 0,
+// rot_cols % 256 == 0, S >= 32.
+bool gemm_mfma_rope_supported(int64_t M, int64_t N, int64_t K, int64_t rot_cols, int S);
+int launch_gemm_mfma_nt_rope(int64_t M, int64_t N, int64_t K, const void* A, int64_t lda, const void* B, int64_t ldb, void* C, int64_t ldc,
+                             const float* rope_table, int S, int64_t rot_cols, hipStream_t st);
 // bf16, head_dim 128, and S * 3 * n_heads * head_dim * 2 bytes below 4 GiB (32-bit row offsets inside one batch element)
 bool attn_mfma_supported(int dtype, int S, int nh, int d);
 int launch_attn_fwd_mfma(int B, int S, int nh, const void* qkv, void* o, float* lse, hipStream_t st);

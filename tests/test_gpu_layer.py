@@ -88,12 +88,14 @@ def test_microbatch_accumulation_matches_oracle_sum(taw):
 
 
 @pytest.mark.parametrize("B,S,nh,I_,sigma", [(1, 256, 2, 384, 0.02), (2, 333, 2, 392, 0.05), (1, 1024, 4, 1408, 0.02), (1, 77, 1, 136, 0.1),
-                                             (1, 256, 2, 400, 0.02)])
+                                             (1, 256, 2, 400, 0.02), (16, 48, 2, 384, 0.05)])
 def test_bf16_layer_on_mfma_kernels(taw, B, S, nh, I_, sigma):
     """bf16, head_dim 128: the MFMA GEMM and attention kernels carry the layer.  Sizes span several
     tiles and leave ragged tails in tokens, widths and the SwiGLU dimension.  The backward linears run
     pairwise in one grid when the token count and the widths are multiples of 32 (first, third and last
-    case; the last with 2 I = 800, which takes the 32-deep input-gradient loop) and one by one otherwise."""
+    case; the fifth with 2 I = 800, which takes the 32-deep input-gradient loop) and one by one otherwise.
+    Where the token count is a multiple of 256 the qkv projection rotates q and k in its epilogue; the
+    last case has sequences of 48 tokens, so the positions wrap inside the 32-row blocks of that epilogue."""
     cfg = I.LayerConfig("bf16-mfma", I.BF16, B, S, nh * 128, nh, 128, I_, sigma_w=sigma)
     U.check_layer(taw, cfg, seed=B + S, gamma_jitter=0.1)
 
