@@ -18,6 +18,7 @@ typedef float f32x16_t __attribute__((ext_vector_type(16)));
 constexpr int kWave = 64;
 
 // ---- V storage elements moved as one vector; kept packed in registers, unpacked on use -------
+// pin(): the compiler must treat the packed value as new from here on, so nothing unpacked from it before stays live
 template <typename T, int V> struct Vec;
 template <> struct Vec<float, 4> {
   f32x4_t raw;
@@ -25,6 +26,7 @@ template <> struct Vec<float, 4> {
   __device__ __forceinline__ void store(float* p) const { *reinterpret_cast<f32x4_t*>(p) = raw; }
   __device__ __forceinline__ float get(int i) const { return raw[i]; }
   __device__ __forceinline__ void set(int i, float x) { raw[i] = x; }
+  __device__ __forceinline__ void pin() { asm volatile("" : "+v"(raw)); }
 };
 template <> struct Vec<float, 1> {
   float raw;
@@ -32,6 +34,7 @@ template <> struct Vec<float, 1> {
   __device__ __forceinline__ void store(float* p) const { *p = raw; }
   __device__ __forceinline__ float get(int) const { return raw; }
   __device__ __forceinline__ void set(int, float x) { raw = x; }
+  __device__ __forceinline__ void pin() { asm volatile("" : "+v"(raw)); }
 };
 template <> struct Vec<bf16_t, 8> {
   bf16x8_t raw;
@@ -39,6 +42,7 @@ template <> struct Vec<bf16_t, 8> {
   __device__ __forceinline__ void store(bf16_t* p) const { *reinterpret_cast<bf16x8_t*>(p) = raw; }
   __device__ __forceinline__ float get(int i) const { return (float)raw[i]; }
   __device__ __forceinline__ void set(int i, float x) { raw[i] = (bf16_t)x; }
+  __device__ __forceinline__ void pin() { asm volatile("" : "+v"(raw)); }
 };
 template <> struct Vec<bf16_t, 1> {
   bf16_t raw;
@@ -46,6 +50,7 @@ template <> struct Vec<bf16_t, 1> {
   __device__ __forceinline__ void store(bf16_t* p) const { *p = raw; }
   __device__ __forceinline__ float get(int) const { return (float)raw; }
   __device__ __forceinline__ void set(int, float x) { raw = (bf16_t)x; }
+  __device__ __forceinline__ void pin() { asm volatile("" : "+v"(raw)); }
 };
 
 template <typename T> struct VecWidth;

@@ -54,25 +54,36 @@ __global__ void __launch_bounds__(256) rmsnorm_fwd_kernel(const T* __restrict__ 
 // its own LDS array (registers would not hold H/64 more floats per lane for wide rows), gamma is
 // read from LDS too.  The four arrays of a workgroup are then summed in a fixed order and written
 // as one partial row, which colsum_kernel reduces.  No atomics: results are reproducible.
-template <typename T, int V, int MAXC>
-__global__ void __launch_bounds__(256) rmsnorm_bwd_kernel(const T* __restrict__ dout, const T* __restrict__ z,
+//
+// REG = true (rows whose sums and packed z, dout take at most 128 registers per lane): the wavefront's column sums stay in registers
+// instead (no LDS read-modify-write per element, and LDS holds only gamma and one row of floats); the
+// wavefronts then add their sums to that row one after the other, in the same fixed order.
+template <typename T, int V, int MAXC, bool REG>
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(REG ? 2 : 1))) rmsnorm_bwd_kernel(const T* __restrict__ dout, const T* __restrict__ z,
                                                           const float* __restrict__ r, const T* __restrict__ gamma,
                                                           const T* __restrict__ dres, T* __restrict__ dz,
                                                           float* __restrict__ partials, int64_t rows, int H) {
   extern __shared__ __attribute__((aligned(16))) unsigned char lds_norm[];
-  float* lds_acc = reinterpret_cast<float*>(lds_norm);            // [4][H]
-  T* lds_g = reinterpret_cast<T*>(lds_acc + 4 * (size_t)H);       // [H]
+  constexpr int NACC = REG ? 1 : 4;
+  float* lds_acc = reinterpret_cast<float*>(lds_norm);               // [NACC][H]
+  T* lds_g = reinterpret_cast<T*>(lds_acc + NACC * (size_t)H);       // [H]
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
   const int nch = H / V;
-  float* my_acc = lds_acc + (size_t)wave * H;
+  float* my_acc = lds_acc + (REG ? 0 : (size_t)wave * H);
+  float racc[REG ? MAXC * V : 1];
   for (int c = threadIdx.x; c < H; c += 256) lds_g[c] = gamma[c];
-  for (int c = lane; c < H; c += 64) my_acc[c] = 0.f;
+  if (REG) {
+#pragma unroll
+    for (int i = 0; i < (REG ? MAXC * V : 1); ++i) racc[i] = 0.f;
+  } else {
+    for (int c = lane; c < H; c += 64) my_acc[c] = 0.f;
+  }
   __syncthreads();
   const float invH = 1.0f / (float)H;
   for (int64_t row = (int64_t)blockIdx.x * 4 + wave; row < rows; row += (int64_t)gridDim.x * 4) {
     const int64_t base = row * (int64_t)H;
-    Vec<T, V> zc[MAXC], dc[MAXC];
+    Vec<T, V> zc[MAXC], dc[MAXC], rs[MAXC];      // the residual gradient is fetched with the row: one memory round trip per row
     float dot = 0.f;
 #pragma unroll
     for (int i = 0; i < MAXC; ++i) {
@@ -80,6 +91,7 @@ __global__ void __launch_bounds__(256) rmsnorm_bwd_kernel(const T* __restrict__ 
       if (ci < nch) {
         zc[i].load(z + base + ci * V);
         dc[i].load(dout + base + ci * V);
+        if (dres) rs[i].load(dres + base + ci * V);
       }
     }
     const float rr = r[row];
@@ -94,9 +106,16 @@ __global__ void __launch_bounds__(256) rmsnorm_bwd_kernel(const T* __restrict__ 
         for (int j = 0; j < V; ++j) {
           const float zz = zc[i].get(j), dd = dc[i].get(j);
           dot += dd * g.get(j) * zz;
-          ap[j] += dd * zz * rr;
+          if (REG) racc[REG ? i * V + j : 0] += dd * zz * rr;
+          else ap[j] += dd * zz * rr;
         }
       }
+    }
+    // only the packed row crosses the reduction
+#pragma unroll
+    for (int i = 0; i < MAXC; ++i) {
+      zc[i].pin();
+      dc[i].pin();
     }
     dot = wave_sum(dot);
     const float coef = rr * rr * rr * dot * invH;
@@ -104,22 +123,42 @@ __global__ void __launch_bounds__(256) rmsnorm_bwd_kernel(const T* __restrict__ 
     for (int i = 0; i < MAXC; ++i) {
       const int ci = i * 64 + lane;
       if (ci < nch) {
-        Vec<T, V> o, res, g;
+        Vec<T, V> o, g;
         g.load(lds_g + ci * V);
-        if (dres) res.load(dres + base + ci * V);
 #pragma unroll
         for (int j = 0; j < V; ++j) {
           float v = rr * dc[i].get(j) * g.get(j) - zc[i].get(j) * coef;
-          if (dres) v += res.get(j);
+          if (dres) v += rs[i].get(j);
           o.set(j, v);
         }
         o.store(dz + base + ci * V);
       }
     }
   }
+  float* prow = partials + (int64_t)blockIdx.x * H;
+  if (REG) {
+    // ((w0 + w1) + w2) + w3, each wavefront adding its registers to the shared row in turn
+    for (int w = 0; w < 4; ++w) {
+      if (wave == w) {
+#pragma unroll
+        for (int i = 0; i < MAXC; ++i) {
+          const int ci = i * 64 + lane;
+          if (ci < nch) {
+#pragma unroll
+            for (int j = 0; j < V; ++j) {
+              const float a = racc[REG ? i * V + j : 0];
+              my_acc[ci * V + j] = w == 0 ? a : my_acc[ci * V + j] + a;
+            }
+          }
+        }
+      }
+      __syncthreads();
+    }
+    for (int c = threadIdx.x; c < H; c += 256) prow[c] = lds_acc[c];
+    return;
+  }
   __syncthreads();
   // fixed-order sum of the four wavefronts' column sums
-  float* prow = partials + (int64_t)blockIdx.x * H;
   for (int c = threadIdx.x; c < H; c += 256)
     prow[c] = ((lds_acc[c] + lds_acc[(size_t)H + c]) + lds_acc[2 * (size_t)H + c]) + lds_acc[3 * (size_t)H + c];
 }
@@ -418,7 +457,7 @@ int launch_rmsnorm_fwd(int dtype, int64_t T_, int H, const void* x, const void* 
   return rmsnorm_fwd_dispatch<float, 1>(T_, H, (const float*)x, (const float*)gamma, eps, (float*)out, r, st);
 }
 
-static constexpr int kNormBwdGrid = 512;
+static constexpr int kNormBwdGrid = 512;      // two workgroups per CU: all resident at once where the register variant runs
 int rmsnorm_bwd_partial_rows() { return kNormBwdGrid; }
 
 template <typename T, int V>
@@ -427,18 +466,22 @@ static int rmsnorm_bwd_dispatch(int64_t T_, int H, const T* dout, const T* z, co
   const int nch = H / V;
   int grid = (int)((T_ + 3) / 4);
   if (grid > kNormBwdGrid) grid = kNormBwdGrid;
-  const size_t lds = 4 * (size_t)H * sizeof(float) + (size_t)H * sizeof(T);      // <= 144 KiB for the widest supported row
-#define TAW_RN_BWD(MAXC)                                                                                                     \
+  // column sums in registers for rows up to 4096 bf16 / 2048 fp32 elements, in LDS (<= 144 KiB for the widest supported row) beyond
+#define TAW_RN_BWD(MAXC, REG)                                                                                                \
   do {                                                                                                                     \
-    hipError_t e_ = hipFuncSetAttribute((const void*)rmsnorm_bwd_kernel<T, V, MAXC>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); \
+    const size_t lds = ((REG) ? 1 : 4) * (size_t)H * sizeof(float) + (size_t)H * sizeof(T);                                  \
+    hipError_t e_ = hipFuncSetAttribute((const void*)rmsnorm_bwd_kernel<T, V, MAXC, REG>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); \
     if (e_ != hipSuccess) return (int)e_;                                                                                   \
-    hipLaunchKernelGGL((rmsnorm_bwd_kernel<T, V, MAXC>), dim3(grid), dim3(256), lds, st, dout, z, r, g, dres, dz, partials, T_, H); \
+    hipLaunchKernelGGL((rmsnorm_bwd_kernel<T, V, MAXC, REG>), dim3(grid), dim3(256), lds, st, dout, z, r, g, dres, dz, partials, T_, H); \
   } while (0)
-  if (nch <= 64) TAW_RN_BWD(1);
-  else if (nch <= 128) TAW_RN_BWD(2);
-  else if (nch <= 256) TAW_RN_BWD(4);
-  else if (nch <= 512) TAW_RN_BWD(8);
-  else TAW_RN_BWD(16);
+  // registers per lane: the sums (one per element) and the packed z and dout rows
+#define TAW_RN_REG(MAXC) ((MAXC) * V * (4 + 2 * (int)sizeof(T)) <= 512)
+  if (nch <= 64) TAW_RN_BWD(1, TAW_RN_REG(1));
+  else if (nch <= 128) TAW_RN_BWD(2, TAW_RN_REG(2));
+  else if (nch <= 256) TAW_RN_BWD(4, TAW_RN_REG(4));
+  else if (nch <= 512) TAW_RN_BWD(8, TAW_RN_REG(8));
+  else TAW_RN_BWD(16, TAW_RN_REG(16));
+#undef TAW_RN_REG
 #undef TAW_RN_BWD
   int e = last_err();
   if (e) return e;
