@@ -18,12 +18,15 @@ typedef float f32x16_t __attribute__((ext_vector_type(16)));
 constexpr int kWave = 64;
 
 // ---- V storage elements moved as one vector; kept packed in registers, unpacked on use -------
+// load_nt / store_nt: non-temporal accesses for data streamed through once
 // pin(): the compiler must treat the packed value as new from here on, so nothing unpacked from it before stays live
 template <typename T, int V> struct Vec;
 template <> struct Vec<float, 4> {
   f32x4_t raw;
   __device__ __forceinline__ void load(const float* p) { raw = *reinterpret_cast<const f32x4_t*>(p); }
   __device__ __forceinline__ void store(float* p) const { *reinterpret_cast<f32x4_t*>(p) = raw; }
+  __device__ __forceinline__ void load_nt(const float* p) { raw = __builtin_nontemporal_load(reinterpret_cast<const f32x4_t*>(p)); }
+  __device__ __forceinline__ void store_nt(float* p) const { __builtin_nontemporal_store(raw, reinterpret_cast<f32x4_t*>(p)); }
   __device__ __forceinline__ float get(int i) const { return raw[i]; }
   __device__ __forceinline__ void set(int i, float x) { raw[i] = x; }
   __device__ __forceinline__ void pin() { asm volatile("" : "+v"(raw)); }
@@ -32,6 +35,8 @@ template <> struct Vec<float, 1> {
   float raw;
   __device__ __forceinline__ void load(const float* p) { raw = *p; }
   __device__ __forceinline__ void store(float* p) const { *p = raw; }
+  __device__ __forceinline__ void load_nt(const float* p) { raw = __builtin_nontemporal_load(p); }
+  __device__ __forceinline__ void store_nt(float* p) const { __builtin_nontemporal_store(raw, p); }
   __device__ __forceinline__ float get(int) const { return raw; }
   __device__ __forceinline__ void set(int, float x) { raw = x; }
   __device__ __forceinline__ void pin() { asm volatile("" : "+v"(raw)); }
@@ -40,6 +45,8 @@ template <> struct Vec<bf16_t, 8> {
   bf16x8_t raw;
   __device__ __forceinline__ void load(const bf16_t* p) { raw = *reinterpret_cast<const bf16x8_t*>(p); }
   __device__ __forceinline__ void store(bf16_t* p) const { *reinterpret_cast<bf16x8_t*>(p) = raw; }
+  __device__ __forceinline__ void load_nt(const bf16_t* p) { raw = __builtin_nontemporal_load(reinterpret_cast<const bf16x8_t*>(p)); }
+  __device__ __forceinline__ void store_nt(bf16_t* p) const { __builtin_nontemporal_store(raw, reinterpret_cast<bf16x8_t*>(p)); }
   __device__ __forceinline__ float get(int i) const { return (float)raw[i]; }
   __device__ __forceinline__ void set(int i, float x) { raw[i] = (bf16_t)x; }
   __device__ __forceinline__ void pin() { asm volatile("" : "+v"(raw)); }
@@ -48,6 +55,8 @@ template <> struct Vec<bf16_t, 1> {
   bf16_t raw;
   __device__ __forceinline__ void load(const bf16_t* p) { raw = *p; }
   __device__ __forceinline__ void store(bf16_t* p) const { *p = raw; }
+  __device__ __forceinline__ void load_nt(const bf16_t* p) { raw = __builtin_nontemporal_load(p); }
+  __device__ __forceinline__ void store_nt(bf16_t* p) const { __builtin_nontemporal_store(raw, p); }
   __device__ __forceinline__ float get(int) const { return (float)raw; }
   __device__ __forceinline__ void set(int, float x) { raw = (bf16_t)x; }
   __device__ __forceinline__ void pin() { asm volatile("" : "+v"(raw)); }

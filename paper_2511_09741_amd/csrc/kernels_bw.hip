@@ -267,15 +267,15 @@ __global__ void __launch_bounds__(256) swiglu_fwd_kernel(const T* __restrict__ g
   const int64_t row = idx / cpr;
   const int col = (int)(idx % cpr) * V;
   Vec<T, V> g, u, o;
-  g.load(gu + row * 2 * (int64_t)I + col);
-  u.load(gu + row * 2 * (int64_t)I + I + col);
+  g.load_nt(gu + row * 2 * (int64_t)I + col);
+  u.load_nt(gu + row * 2 * (int64_t)I + I + col);
 #pragma unroll
   for (int j = 0; j < V; ++j) {
     const float gg = g.get(j);
     const float sig = 1.0f / (1.0f + __expf(-gg));
     o.set(j, gg * sig * u.get(j));
   }
-  o.store(a + row * (int64_t)I + col);
+  o.store_nt(a + row * (int64_t)I + col);
 }
 
 // dg = da u sig (1 + g (1 - sig));  du = da g sig
@@ -288,9 +288,9 @@ __global__ void __launch_bounds__(256) swiglu_bwd_kernel(const T* __restrict__ d
   const int64_t row = idx / cpr;
   const int col = (int)(idx % cpr) * V;
   Vec<T, V> g, u, d, og, ou;
-  g.load(gu + row * 2 * (int64_t)I + col);
-  u.load(gu + row * 2 * (int64_t)I + I + col);
-  d.load(da + row * (int64_t)I + col);
+  g.load_nt(gu + row * 2 * (int64_t)I + col);
+  u.load_nt(gu + row * 2 * (int64_t)I + I + col);
+  d.load_nt(da + row * (int64_t)I + col);
 #pragma unroll
   for (int j = 0; j < V; ++j) {
     const float gg = g.get(j), dd = d.get(j);
@@ -298,8 +298,8 @@ __global__ void __launch_bounds__(256) swiglu_bwd_kernel(const T* __restrict__ d
     og.set(j, dd * u.get(j) * sig * (1.0f + gg * (1.0f - sig)));
     ou.set(j, dd * gg * sig);
   }
-  og.store(dgu + row * 2 * (int64_t)I + col);
-  ou.store(dgu + row * 2 * (int64_t)I + I + col);
+  og.store_nt(dgu + row * 2 * (int64_t)I + col);
+  ou.store_nt(dgu + row * 2 * (int64_t)I + I + col);
 }
 
 // =============================================================================== gradient accumulation
