@@ -43,7 +43,7 @@ PEAK_HBM_GBS = 8000.0
 # HBM-side bytes per GEMM launch (average of the 12 shapes of a step), from two rocprofv3 --pmc runs of this file
 # (FETCH_SIZE, WRITE_SIZE; each scaled by what the counter reads for the staging copy kernel, a plain copy of
 # known size): profiles/gemm_C2_hbm_traffic.md.  Only measured for the workload named.
-GEMM_TRAFFIC_BYTES_PER_LAUNCH = {"C2": 1452.9e6}
+GEMM_TRAFFIC_BYTES_PER_LAUNCH = {"C2": 1459.7e6}
 # the paper's throughput table (Experiments, Throughput and Memory Usage): micro-batch size per sequence length and
 # TawPipe's tokens per GPU per second on its own hardware
 PAPER_TABLE_B = {4096: 16, 8192: 8, 16384: 4}

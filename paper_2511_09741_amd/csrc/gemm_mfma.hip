@@ -366,6 +366,8 @@ __device__ constexpr int kReadOrder[8] = {0, 4, 5, 1, 6, 2, 7, 3};
 
 // ---- the same for a tile that lies wholly inside C with 16-byte aligned row segments (all tiles of
 // the layer's shapes): no per-element checks, 32-bit lane offsets from the wavefront's corner of C
+// The result is stored non-temporally: a round of tiles writes more than an L2 holds, and ordinary stores
+// push the operand panels out of it (1-3 % per GEMM).
 //
 // EPI = kEpiRope (bf16 output only): the rotary embedding applied to the result before it is stored.
 // Columns below rot_cols are heads of 128 whose adjacent pairs (2i, 2i+1) are rotated by the angle of
@@ -414,7 +416,7 @@ __device__ __forceinline__ void store_tile_full(const f32x16_t (&acc)[4][4], uns
         f32x4_t v = *reinterpret_cast<const f32x4_t*>(sp);
         if (ri) v += *reinterpret_cast<const f32x4_t*>(ri + roff0 + it * rstep);
         if (accumulate) v += *reinterpret_cast<const f32x4_t*>(ci + coff0 + it * cstep);
-        *reinterpret_cast<f32x4_t*>(ci + coff0 + it * cstep) = v;
+        __builtin_nontemporal_store(v, reinterpret_cast<f32x4_t*>(ci + coff0 + it * cstep));
       } else {
         const f32x4_t v0 = *reinterpret_cast<const f32x4_t*>(sp), v1 = *reinterpret_cast<const f32x4_t*>(sp + 4);
         float v[8] = {v0[0], v0[1], v0[2], v0[3], v1[0], v1[1], v1[2], v1[3]};
@@ -446,7 +448,7 @@ __device__ __forceinline__ void store_tile_full(const f32x16_t (&acc)[4][4], uns
         bf16x8_t o;
 #pragma unroll
         for (int e = 0; e < 8; ++e) o[e] = (bf16_t)v[e];
-        *reinterpret_cast<bf16x8_t*>(ci + coff0 + it * cstep) = o;
+        __builtin_nontemporal_store(o, reinterpret_cast<bf16x8_t*>(ci + coff0 + it * cstep));
       }
     }
     __builtin_amdgcn_s_waitcnt(0xc07f);
