@@ -206,7 +206,7 @@ def test_attention_generic(taw, dtype, B, S, nh, d):
 
 
 @pytest.mark.parametrize("src_dtype", [I.F32, I.BF16])
-@pytest.mark.parametrize("n", [0, 1, 3, 4, 1027, 1 << 20])
+@pytest.mark.parametrize("n", [0, 1, 3, 4, 1027, 13490, 1 << 20])      # 13490: whole workgroups, a partly filled one and a scalar tail
 def test_grad_accum(taw, src_dtype, n):
     import torch
     rng = np.random.default_rng(n + 1)
@@ -295,7 +295,7 @@ def test_attention_mfma_peaked_scores(taw):
 
 
 @pytest.mark.parametrize("dtype", [I.F32, I.BF16])
-@pytest.mark.parametrize("n", [1, 7, 4096, 1 << 20])
+@pytest.mark.parametrize("n", [1, 7, 4096, 4499, 1 << 20])           # 4499: whole workgroups, a partly filled one and a scalar tail
 def test_optimizer_step(taw, dtype, n):
     """Three AdamW steps over a shard against the oracle: master weights, both moments, the chunk in its
     storage type, and the zeroed gradient shard."""
