@@ -287,7 +287,7 @@ def main():
         lse = torch.empty(cfg.B * cfg.n_heads * cfg.S, dtype=torch.float32, device="cuda")
         scr = torch.empty(taw.taw_op_attn_bwd_scratch_floats(cfg.B, cfg.S, cfg.n_heads), dtype=torch.float32, device="cuda")
         tf = ev_time(lambda: taw.taw_op_attn_fwd(BF, cfg.B, cfg.S, cfg.n_heads, cfg.head_dim, qkv, o, lse, taw.TAW_IMPL_MFMA, compute), 3)
-        tb = ev_time(lambda: taw.taw_op_attn_bwd(BF, cfg.B, cfg.S, cfg.n_heads, cfg.head_dim, qkv, o, dO, lse, dqkv, scr, taw.TAW_IMPL_MFMA, compute), 3)
+        tb = ev_time(lambda: taw.taw_op_attn_bwd(BF, cfg.B, cfg.S, cfg.n_heads, cfg.head_dim, qkv, o, dO, lse, dqkv, scr, None, taw.TAW_IMPL_MFMA, compute), 3)
         kernels["attn_fwd"] = {"ms": round(tf, 4), "model_TFLOPs": round(attn_fl / 3 / tf / 1e9, 1)}
         kernels["attn_bwd"] = {"ms": round(tb, 4), "model_TFLOPs": round(attn_fl * 2 / 3 / tb / 1e9, 1)}
         # bandwidth kernels: algorithmic bytes / time

@@ -135,9 +135,9 @@ int taw_grad_accum(float* G_dst, const void* g_src, int32_t src_dtype, size_t n_
 int taw_weight_stage(void* dst_buf, const void* src_shard, size_t bytes, void* copy_stream,
                      void* wait_event, void* ready_event);
 
-/* Owner-side update of a weight shard from its aggregated gradient shard ("updates are applied
- * locally using colocated optimizer states", Methodology, Group-Based Weight Pipeline Scheduler).
- * The paper does not name the optimizer; this is AdamW (decoupled weight decay), one pass over the
+/* Owner-side update of a weight shard from its aggregated gradient shard: the owner keeps the
+ * optimizer state next to its shard and updates in place, with no further communication
+ * (Methodology, Group-Based Weight Pipeline Scheduler).  The paper does not name the optimizer; this is AdamW (decoupled weight decay), one pass over the
  * shard, for step number `step` (1-based):
  *   g = grad_scale * G[i];  m = beta1 m + (1-beta1) g;  v = beta2 v + (1-beta2) g^2;
  *   w = w - lr * ( (m / (1-beta1^step)) / (sqrt(v / (1-beta2^step)) + eps) + weight_decay * w )

@@ -65,12 +65,31 @@ int taw_op_attn_fwd(int32_t dtype, int32_t B, int32_t S, int32_t n_heads, int32_
                     void* o, float* lse, int32_t impl, void* stream);
 
 /* Its gradient: dqkv [B*S, 3H] from dO [B*S, H], recomputing the probabilities from qkv and lse.
- * scratch: fp32, taw_op_attn_bwd_scratch_floats(B, S, n_heads) elements (holds the row statistics
- * D[t] = dO[t].o[t] and a rescaled copy of lse, padded per head). */
+ * rope_table (may be NULL): when given (fp32 [S, head_dim/2, 2] from taw_rope_table_init), q and k
+ * are taken to be rotated and dq, dk come out as the gradients of the unrotated q, k (the rotary
+ * backward, a rotation by the opposite angle, applied before the store); NULL leaves them as the
+ * gradients of the q, k passed in.
+ * scratch: fp32, taw_op_attn_bwd_scratch_floats(B, S, n_heads) elements (row statistics
+ * D[t] = dO[t].o[t], a rescaled copy of lse, and the fp32 accumulator of dq; contents are
+ * overwritten, nothing has to be cleared by the caller). */
 size_t taw_op_attn_bwd_scratch_floats(int32_t B, int32_t S, int32_t n_heads);
 int taw_op_attn_bwd(int32_t dtype, int32_t B, int32_t S, int32_t n_heads, int32_t head_dim, const void* qkv,
                     const void* o, const void* dO, const float* lse, void* dqkv, float* scratch,
-                    int32_t impl, void* stream);
+                    const float* rope_table, int32_t impl, void* stream);
+
+/* The fused qkv projection with the rotary embedding, as taw_layer_fwd runs it:
+ *   qkv [B*S, 3H] = xn [B*S, H] w_qkv[3H, H]^T, then q and k (columns 0 .. 2H-1) rotated by position.
+ * On the MFMA path the rotation happens in the GEMM's epilogue when B*S and H allow it (otherwise,
+ * and on the generic path, a rotary pass follows the GEMM: same result up to one more rounding). */
+int taw_op_qkv_rope(int32_t dtype, int32_t B, int32_t S, int32_t n_heads, int32_t head_dim, const void* xn,
+                    const void* w_qkv, void* qkv, const float* rope_table, int32_t impl, void* stream);
+
+/* Backward of a linear y [T, N] = x [T, K] W[N, K]^T given dy, as taw_layer_bwd runs it:
+ *   dx [T, K] = dy W              (storage type dtype)
+ *   G  [N, K] (=|+=) dy^T x       (fp32; += when accumulate != 0)
+ * On the MFMA path the two products share one grid when T and N are multiples of 32. */
+int taw_op_linear_bwd(int32_t dtype, int64_t T, int64_t N, int64_t K, const void* dy, const void* W, const void* x,
+                      void* dx, float* G, int32_t accumulate, int32_t impl, void* stream);
 
 #ifdef __cplusplus
 }

@@ -220,9 +220,9 @@ def grad_accum(G_dst, g_src, scale=1.0):
 
 
 def adamw_step(w, m, v, g, step, lr, beta1, beta2, eps, weight_decay, grad_scale=1.0):
-    """Owner-side update of a shard (Methodology, GWPS: "updates are applied locally using colocated
-    optimizer states"; the optimizer itself is not named by the paper: AdamW with decoupled weight
-    decay is the reading adopted).  All arrays fp64; step is 1-based.  Returns (w, m, v) after the step:
+    """Owner-side update of a shard (Methodology, GWPS: the owner updates its shard in place from the
+    optimizer state it keeps beside it; the optimizer itself is not named by the paper: AdamW with
+    decoupled weight decay is the reading adopted).  All arrays fp64; step is 1-based.  Returns (w, m, v) after the step:
       g' = grad_scale g;  m = b1 m + (1-b1) g';  v = b2 v + (1-b2) g'^2
       w = w - lr ( m/(1-b1^t) / (sqrt(v/(1-b2^t)) + eps) + weight_decay w )"""
     g = grad_scale * g
@@ -302,6 +302,63 @@ def attention_bwd_tail(q, k, v, do, t0):
     dk = (dS[:, t0:].T @ q[t0:]) * scale
     dv = P[:, t0:].T @ do[t0:]
     return dq, dk, dv
+
+
+def layer_bwd_tail(W, x, dy, t0, n_heads, rope_theta=10000.0, rms_eps=1e-6):
+    """dx at the token rows t >= t0 of ONE batch element, by the same definitions as layer_fwd / layer_bwd.
+    x, dy: [S, H].  Causality makes this a closed sub-problem: the forward at a row t >= t0 needs the
+    keys and values of every row (projected here for all of them) but queries, attention and the MLP
+    only at the rows t >= t0; in the backward, dq[t] needs row t of the probabilities only, and
+    dk[u], dv[u] for u >= t0 receive contributions from the queries t >= u >= t0 only.  Everything
+    else (the residual path, both norms, the MLP) is row-wise.  Returns dx[t0:] as [S - t0, H]."""
+    S, H = x.shape
+    d = H // n_heads
+    I = W["w_down"].shape[1]
+    n = S - t0
+    scale = 1.0 / np.sqrt(d)
+    # ---- forward: k, v everywhere; the rest at rows t0..S-1
+    xn, r1 = rmsnorm_fwd(x, W["gamma_attn"], rms_eps)
+    phi = rope_angles(S, d, rope_theta)
+    k = rope_apply((xn @ W["w_qkv"][H:2 * H].T).reshape(1, S, n_heads, d), phi)[0]
+    v = (xn @ W["w_qkv"][2 * H:].T).reshape(S, n_heads, d)
+    q = rope_apply((xn[t0:] @ W["w_qkv"][:H].T).reshape(1, n, n_heads, d), phi[t0:])[0]
+    rows = np.arange(t0, S)
+    P = np.empty((n_heads, n, S))
+    o = np.empty((n, n_heads, d))
+    for h in range(n_heads):
+        sc = (q[:, h, :] @ k[:, h, :].T) * scale
+        sc = np.where(np.arange(S)[None, :] <= rows[:, None], sc, -np.inf)
+        e = np.exp(sc - sc.max(axis=1, keepdims=True))
+        P[h] = e / e.sum(axis=1, keepdims=True)
+        o[:, h, :] = P[h] @ v[:, h, :]
+    o2 = o.reshape(n, H)
+    hrow = x[t0:] + o2 @ W["w_o"].T
+    hn, r2 = rmsnorm_fwd(hrow, W["gamma_mlp"], rms_eps)
+    gu = hn @ W["w_gate_up"].T
+    g, u = gu[:, :I], gu[:, I:]
+    # ---- backward at the same rows
+    dyt = dy[t0:]
+    da = dyt @ W["w_down"]
+    dg, du = swiglu_bwd(da, g, u)
+    dhn = np.concatenate([dg, du], axis=1) @ W["w_gate_up"]
+    dz, _ = rmsnorm_bwd(dhn, hrow, r2, W["gamma_mlp"])
+    dh = dyt + dz
+    do = (dh @ W["w_o"]).reshape(n, n_heads, d)
+    dq = np.empty((n, n_heads, d))
+    dk = np.empty((n, n_heads, d))
+    dv = np.empty((n, n_heads, d))
+    for h in range(n_heads):
+        D = np.sum(do[:, h, :] * o[:, h, :], axis=1, keepdims=True)
+        dS = P[h] * (do[:, h, :] @ v[:, h, :].T - D)
+        dq[:, h, :] = (dS @ k[:, h, :]) * scale
+        dk[:, h, :] = (dS[:, t0:].T @ q[:, h, :]) * scale
+        dv[:, h, :] = P[h][:, t0:].T @ do[:, h, :]
+    dq = rope_apply(dq[None], phi[t0:], inverse=True)[0]
+    dk = rope_apply(dk[None], phi[t0:], inverse=True)[0]
+    dqkv = np.concatenate([dq.reshape(n, H), dk.reshape(n, H), dv.reshape(n, H)], axis=1)
+    dxn = dqkv @ W["w_qkv"]
+    dz, _ = rmsnorm_bwd(dxn, x[t0:], r1[t0:], W["gamma_attn"])
+    return dh + dz
 
 
 def flops_fwd_bwd(B, S, H, I):

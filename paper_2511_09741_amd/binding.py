@@ -78,7 +78,9 @@ _SIGS = {
     "taw_op_swiglu_fwd": (C.c_int, [_i32, _i64, _i32, _vp, _vp, _vp]),
     "taw_op_swiglu_bwd": (C.c_int, [_i32, _i64, _i32, _vp, _vp, _vp, _vp]),
     "taw_op_attn_fwd": (C.c_int, [_i32, _i32, _i32, _i32, _i32, _vp, _vp, _vp, _i32, _vp]),
-    "taw_op_attn_bwd": (C.c_int, [_i32, _i32, _i32, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _vp]),
+    "taw_op_attn_bwd": (C.c_int, [_i32, _i32, _i32, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _vp]),
+    "taw_op_qkv_rope": (C.c_int, [_i32, _i32, _i32, _i32, _i32, _vp, _vp, _vp, _vp, _i32, _vp]),
+    "taw_op_linear_bwd": (C.c_int, [_i32, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _vp]),
 }
 EXPORTS = tuple(_SIGS)
 
@@ -269,6 +271,14 @@ def taw_op_attn_bwd_scratch_floats(B, S, n_heads) -> int:
     return int(load().taw_op_attn_bwd_scratch_floats(B, S, n_heads))
 
 
-def taw_op_attn_bwd(dtype, B, S, n_heads, head_dim, qkv, o, dO, lse, dqkv, scratch, impl=TAW_IMPL_AUTO, stream=None):
-    _check(load().taw_op_attn_bwd(dtype, B, S, n_heads, head_dim, _p(qkv), _p(o), _p(dO), _p(lse), _p(dqkv), _p(scratch), impl,
-                                  _stream(stream)))
+def taw_op_attn_bwd(dtype, B, S, n_heads, head_dim, qkv, o, dO, lse, dqkv, scratch, rope_table=None, impl=TAW_IMPL_AUTO, stream=None):
+    _check(load().taw_op_attn_bwd(dtype, B, S, n_heads, head_dim, _p(qkv), _p(o), _p(dO), _p(lse), _p(dqkv), _p(scratch),
+                                  _p(rope_table), impl, _stream(stream)))
+
+
+def taw_op_qkv_rope(dtype, B, S, n_heads, head_dim, xn, w_qkv, qkv, rope_table, impl=TAW_IMPL_AUTO, stream=None):
+    _check(load().taw_op_qkv_rope(dtype, B, S, n_heads, head_dim, _p(xn), _p(w_qkv), _p(qkv), _p(rope_table), impl, _stream(stream)))
+
+
+def taw_op_linear_bwd(dtype, T, N, K, dy, W, x, dx, G, accumulate=0, impl=TAW_IMPL_AUTO, stream=None):
+    _check(load().taw_op_linear_bwd(dtype, T, N, K, _p(dy), _p(W), _p(x), _p(dx), _p(G), accumulate, impl, _stream(stream)))

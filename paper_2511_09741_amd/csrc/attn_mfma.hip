@@ -771,8 +771,7 @@ int launch_fwd(int B, int S, int nh, const void* qkv, void* o, float* lse, hipSt
   constexpr int BQ = 256;
   constexpr size_t lds = 4 * 2 * kTileBytes;      // the ring; the output staging (8 x 32 x 136 bf16) fits inside
   static_assert(lds >= 8 * 32 * 136 * sizeof(bf16_t), "staging area");
-  hipError_t e = hipFuncSetAttribute((const void*)attn_fwd_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-  if (e != hipSuccess) return (int)e;
+  TAW_SET_LDS_LIMIT_ONCE(attn_fwd_kernel, lds);
   const int nqt = (S + BQ - 1) / BQ;
   const float scale = 1.0f / sqrtf((float)D);
   hipLaunchKernelGGL(attn_fwd_kernel, dim3((unsigned)(nqt * B * nh)), dim3(kThreads8), lds, st, (const bf16_t*)qkv, (bf16_t*)o, lse, B, S, nh, scale);
@@ -807,8 +806,7 @@ int launch_attn_bwd_mfma(int B, int S, int nh, const void* qkv, const void* o, c
   {
     constexpr size_t lds = 4 * (2 * kTileBytes + 2 * 64 * sizeof(float));
     static_assert(lds >= 8 * 32 * 136 * sizeof(bf16_t), "staging area");
-    hipError_t e = hipFuncSetAttribute((const void*)attn_bwd_dkv_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e != hipSuccess) return (int)e;
+    TAW_SET_LDS_LIMIT_ONCE(attn_bwd_dkv_kernel, lds);
     const int nkt = (S + 255) / 256;
     hipLaunchKernelGGL(attn_bwd_dkv_kernel, dim3((unsigned)(nkt * B * nh)), dim3(kThreads8), lds, st, (const bf16_t*)qkv, (const bf16_t*)dO, lse2, Dv,
                        (bf16_t*)dqkv, B, S, Sp, nh, scale, rope_table);
@@ -817,8 +815,7 @@ int launch_attn_bwd_mfma(int B, int S, int nh, const void* qkv, const void* o, c
   }
   {
     constexpr size_t lds = 4 * 2 * kTileBytes;
-    hipError_t e = hipFuncSetAttribute((const void*)attn_bwd_dq_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e != hipSuccess) return (int)e;
+    TAW_SET_LDS_LIMIT_ONCE(attn_bwd_dq_kernel, lds);
     const int nqt = (S + 255) / 256;
     hipLaunchKernelGGL(attn_bwd_dq_kernel, dim3((unsigned)(nqt * B * nh)), dim3(kThreads8), lds, st, (const bf16_t*)qkv, (const bf16_t*)dO, lse2, Dv,
                        (bf16_t*)dqkv, B, S, Sp, nh, scale, rope_table);

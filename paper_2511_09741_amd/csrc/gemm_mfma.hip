@@ -943,25 +943,14 @@ static_assert(kLds64 == kLds2, "the two pipelined kernels share one LDS size");
 
 template <int MODE, bool C_F32, bool K64, int EPI = kEpiNone>
 int launch_pipe(const GemmArgs& g, hipStream_t st) {
-  static bool attr_set = false;   // per instantiation; setting it again is harmless
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void*)gemm_pipe_kernel<MODE, C_F32, K64, EPI>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLds2);
-    if (e != hipSuccess) return (int)e;
-    attr_set = true;
-  }
+  TAW_SET_LDS_LIMIT_ONCE((gemm_pipe_kernel<MODE, C_F32, K64, EPI>), kLds2);
   hipLaunchKernelGGL((gemm_pipe_kernel<MODE, C_F32, K64, EPI>), dim3((unsigned)(g.tiles_m * g.tiles_n)), dim3(kThreads), kLds2, st, g);
   return (int)hipGetLastError();
 }
 
 template <int MODE0, bool F32_0, bool K64_0, int MODE1, bool F32_1, bool K64_1>
 int launch_dual(const GemmArgs& g0, const GemmArgs& g1, hipStream_t st) {
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void*)gemm_dual_kernel<MODE0, F32_0, K64_0, MODE1, F32_1, K64_1>,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLds2);
-    if (e != hipSuccess) return (int)e;
-    attr_set = true;
-  }
+  TAW_SET_LDS_LIMIT_ONCE((gemm_dual_kernel<MODE0, F32_0, K64_0, MODE1, F32_1, K64_1>), kLds2);
   const int n0 = g0.tiles_m * g0.tiles_n, n1 = g1.tiles_m * g1.tiles_n;
   hipLaunchKernelGGL((gemm_dual_kernel<MODE0, F32_0, K64_0, MODE1, F32_1, K64_1>), dim3((unsigned)(n0 + n1)), dim3(kThreads), kLds2, st, g0, g1, n0);
   return (int)hipGetLastError();
@@ -972,12 +961,7 @@ int launch_dual(const GemmArgs& g0, const GemmArgs& g1, hipStream_t st) {
 template <int MODE, bool C_F32>
 int launch_t(int64_t M, int64_t N, int64_t K, const void* A, int64_t lda, const void* B, int64_t ldb, void* C, int64_t ldc,
              int accumulate, const void* R, int64_t ldr, hipStream_t st) {
-  static bool attr_set = false;   // per instantiation; setting it again is harmless
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void*)gemm_mfma_kernel<MODE, C_F32>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsBytes);
-    if (e != hipSuccess) return (int)e;
-    attr_set = true;
-  }
+  TAW_SET_LDS_LIMIT_ONCE((gemm_mfma_kernel<MODE, C_F32>), kLdsBytes);
   const int tiles_m = (int)((M + BM - 1) / BM), tiles_n = (int)((N + BN - 1) / BN);
   hipLaunchKernelGGL((gemm_mfma_kernel<MODE, C_F32>), dim3((unsigned)(tiles_m * tiles_n)), dim3(kThreads), kLdsBytes, st, M, N, K,
                      (const bf16_t*)A, lda, (const bf16_t*)B, ldb, C, ldc, accumulate, R, ldr, tiles_m, tiles_n);

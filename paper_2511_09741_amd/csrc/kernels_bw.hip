@@ -505,8 +505,8 @@ static int rmsnorm_bwd_dispatch(int64_t T_, int H, const T* dout, const T* z, co
 #define TAW_RN_BWD(MAXC, REG)                                                                                                \
   do {                                                                                                                     \
     const size_t lds = ((REG) ? 1 : 4) * (size_t)H * sizeof(float) + (size_t)H * sizeof(T);                                  \
-    hipError_t e_ = hipFuncSetAttribute((const void*)rmsnorm_bwd_kernel<T, V, MAXC, REG>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); \
-    if (e_ != hipSuccess) return (int)e_;                                                                                   \
+    /* the widest row this instantiation takes is MAXC * 64 * V elements */                                                  \
+    TAW_SET_LDS_LIMIT_ONCE((rmsnorm_bwd_kernel<T, V, MAXC, REG>), (((REG) ? 1 : 4) * sizeof(float) + sizeof(T)) * (size_t)(MAXC) * 64 * V); \
     hipLaunchKernelGGL((rmsnorm_bwd_kernel<T, V, MAXC, REG>), dim3(grid), dim3(256), lds, st, dout, z, r, g, dres, dz, partials, T_, H); \
   } while (0)
   // registers per lane: the sums (one per element) and the packed z and dout rows

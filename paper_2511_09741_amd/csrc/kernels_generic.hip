@@ -218,8 +218,7 @@ static int attn_fwd_generic_t(int B, int S, int nh, int d, const T* qkv, T* o, f
   const int64_t total = (int64_t)B * nh * S;
   if (total == 0) return 0;
   const size_t lds = (size_t)4 * S * sizeof(float);
-  hipError_t e = hipFuncSetAttribute((const void*)attn_fwd_generic_kernel<T>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-  if (e != hipSuccess) return (int)e;
+  TAW_SET_LDS_LIMIT_ONCE((attn_fwd_generic_kernel<T>), (size_t)4 * kGenAttnMaxS * sizeof(float));
   hipLaunchKernelGGL((attn_fwd_generic_kernel<T>), dim3((unsigned)((total + 3) / 4)), dim3(256), lds, st, qkv, o, lse, B, S, nh, d);
   return (int)hipGetLastError();
 }
@@ -236,14 +235,12 @@ static int attn_bwd_generic_t(int B, int S, int nh, int d, const T* qkv, const T
   if (total == 0) return 0;
   const unsigned grid = (unsigned)((total + 3) / 4);
   size_t lds = (size_t)4 * S * sizeof(float);
-  hipError_t e = hipFuncSetAttribute((const void*)attn_bwd_dq_generic_kernel<T>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-  if (e != hipSuccess) return (int)e;
+  TAW_SET_LDS_LIMIT_ONCE((attn_bwd_dq_generic_kernel<T>), (size_t)4 * kGenAttnMaxS * sizeof(float));
   hipLaunchKernelGGL((attn_bwd_dq_generic_kernel<T>), dim3(grid), dim3(256), lds, st, qkv, dO, lse, D, dqkv, B, S, nh, d);
   int rc = (int)hipGetLastError();
   if (rc) return rc;
   lds *= 2;
-  e = hipFuncSetAttribute((const void*)attn_bwd_dkv_generic_kernel<T>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-  if (e != hipSuccess) return (int)e;
+  TAW_SET_LDS_LIMIT_ONCE((attn_bwd_dkv_generic_kernel<T>), (size_t)8 * kGenAttnMaxS * sizeof(float));
   hipLaunchKernelGGL((attn_bwd_dkv_generic_kernel<T>), dim3(grid), dim3(256), lds, st, qkv, dO, lse, D, dqkv, B, S, nh, d);
   return (int)hipGetLastError();
 }

@@ -476,20 +476,71 @@ extern "C" size_t taw_op_attn_bwd_scratch_floats(int32_t B, int32_t S, int32_t n
 }
 
 extern "C" int taw_op_attn_bwd(int32_t dtype, int32_t B, int32_t S, int32_t n_heads, int32_t head_dim, const void* qkv, const void* o,
-                               const void* dO, const float* lse, void* dqkv, float* scratch, int32_t impl, void* stream) {
+                               const void* dO, const float* lse, void* dqkv, float* scratch, const float* rope_table, int32_t impl,
+                               void* stream) {
   bool mf;
   int rc = check_attn(dtype, B, S, n_heads, head_dim, impl, &mf);
   if (rc) return rc;
   TAW_REQUIRE_PTR(qkv); TAW_REQUIRE_PTR(o); TAW_REQUIRE_PTR(dO); TAW_REQUIRE_PTR(lse); TAW_REQUIRE_PTR(dqkv); TAW_REQUIRE_PTR(scratch);
   TAW_REQUIRE_ALIGNED(qkv); TAW_REQUIRE_ALIGNED(o); TAW_REQUIRE_ALIGNED(dO); TAW_REQUIRE_ALIGNED(lse); TAW_REQUIRE_ALIGNED(dqkv);
-  TAW_REQUIRE_ALIGNED(scratch);
+  TAW_REQUIRE_ALIGNED(scratch); TAW_REQUIRE_ALIGNED(rope_table);
   const hipStream_t st = (hipStream_t)stream;
   const int64_t H = (int64_t)n_heads * head_dim;
   if (mf) {
-    TAW_LAUNCH(launch_attn_bwd_mfma(B, S, n_heads, qkv, o, dO, lse, scratch, dqkv, nullptr, st), "attention bwd (mfma)");
+    TAW_LAUNCH(launch_attn_bwd_mfma(B, S, n_heads, qkv, o, dO, lse, scratch, dqkv, rope_table, st), "attention bwd (mfma)");
   } else {
     TAW_LAUNCH(launch_attn_rowdot(dtype, B, S, n_heads, head_dim, o, H, dO, H, scratch, st), "attention row dot");
     TAW_LAUNCH(launch_attn_bwd_generic(dtype, B, S, n_heads, head_dim, qkv, dO, lse, scratch, dqkv, st), "attention bwd (generic)");
+    if (rope_table) TAW_LAUNCH(launch_rope(dtype, B, S, (int)(2 * H), head_dim, dqkv, 3 * H, rope_table, 1, st), "rope bwd");
   }
+  return TAW_OK;
+}
+
+extern "C" int taw_op_qkv_rope(int32_t dtype, int32_t B, int32_t S, int32_t n_heads, int32_t head_dim, const void* xn, const void* w_qkv,
+                               void* qkv, const float* rope_table, int32_t impl, void* stream) {
+  int rc = check_dtype(dtype);
+  if (rc) return rc;
+  if (B <= 0 || S <= 0 || n_heads <= 0 || head_dim <= 0 || head_dim % 2) return fail(TAW_ERR_SHAPE, "bad shape (B=%d S=%d n_heads=%d head_dim=%d)", B, S, n_heads, head_dim);
+  if ((int64_t)B * S > (int64_t)1 << 24) return fail(TAW_ERR_SHAPE, "B*S exceeds 2^24 tokens");
+  TAW_REQUIRE_PTR(xn); TAW_REQUIRE_PTR(w_qkv); TAW_REQUIRE_PTR(qkv); TAW_REQUIRE_PTR(rope_table);
+  TAW_REQUIRE_ALIGNED(xn); TAW_REQUIRE_ALIGNED(w_qkv); TAW_REQUIRE_ALIGNED(qkv); TAW_REQUIRE_ALIGNED(rope_table);
+  const hipStream_t st = (hipStream_t)stream;
+  const int64_t T = (int64_t)B * S, H = (int64_t)n_heads * head_dim;
+  const bool can = gemm_mfma_supported(dtype, GEMM_NT, T, 3 * H, H, H, H, 3 * H, dtype, 0);
+  if (impl == TAW_IMPL_MFMA && !can) return fail(TAW_ERR_UNSUPPORTED, "MFMA GEMM needs bf16 and H a multiple of 8");
+  if (impl != TAW_IMPL_GENERIC && can) {
+    if (head_dim == 128 && gemm_mfma_rope_supported(T, 3 * H, H, 2 * H, S)) {
+      TAW_LAUNCH(launch_gemm_mfma_nt_rope(T, 3 * H, H, xn, H, w_qkv, H, qkv, 3 * H, rope_table, S, 2 * H, st), "gemm qkv + rope");
+      return TAW_OK;
+    }
+    TAW_LAUNCH(launch_gemm_mfma(GEMM_NT, T, 3 * H, H, xn, H, w_qkv, H, qkv, 3 * H, dtype, 0, nullptr, 0, st), "gemm qkv (mfma)");
+  } else {
+    TAW_LAUNCH(launch_gemm_generic(dtype, GEMM_NT, T, 3 * H, H, xn, H, w_qkv, H, qkv, 3 * H, dtype, 0, nullptr, 0, st), "gemm qkv (generic)");
+  }
+  TAW_LAUNCH(launch_rope(dtype, B, S, (int)(2 * H), head_dim, qkv, 3 * H, rope_table, 0, st), "rope");
+  return TAW_OK;
+}
+
+extern "C" int taw_op_linear_bwd(int32_t dtype, int64_t T, int64_t N, int64_t K, const void* dy, const void* W, const void* x, void* dx,
+                                 float* G, int32_t accumulate, int32_t impl, void* stream) {
+  int rc = check_dtype(dtype);
+  if (rc) return rc;
+  if (T < 0 || N < 0 || K < 0) return fail(TAW_ERR_SHAPE, "negative dimension");
+  if (impl < TAW_IMPL_AUTO || impl > TAW_IMPL_MFMA) return fail(TAW_ERR_SHAPE, "unknown impl %d", impl);
+  if (K == 0 || (T == 0 && N == 0)) return TAW_OK;
+  if (T > 0) { TAW_REQUIRE_PTR(dx); TAW_REQUIRE_ALIGNED(dx); }
+  if (N > 0) { TAW_REQUIRE_PTR(G); TAW_REQUIRE_ALIGNED(G); }
+  if (T > 0 && N > 0) {
+    TAW_REQUIRE_PTR(dy); TAW_REQUIRE_PTR(W); TAW_REQUIRE_PTR(x);
+    TAW_REQUIRE_ALIGNED(dy); TAW_REQUIRE_ALIGNED(W); TAW_REQUIRE_ALIGNED(x);
+  }
+  const hipStream_t st = (hipStream_t)stream;
+  const bool can = T > 0 && N > 0 && gemm_mfma_supported(dtype, GEMM_NN, T, K, N, N, K, K, dtype, 0) &&
+                   gemm_mfma_supported(dtype, GEMM_TN, N, K, T, N, K, K, DT_F32, 0);
+  if (impl == TAW_IMPL_MFMA && !can) return fail(TAW_ERR_UNSUPPORTED, "MFMA GEMMs need bf16 and N, K multiples of 8");
+  Plan p;
+  p.mfma_gemm = can && impl != TAW_IMPL_GENERIC;
+  p.mfma_attn = false;
+  TAW_LAUNCH(linear_bwd(p, dtype, T, N, K, dy, W, x, dx, G, accumulate ? 1 : 0, st), "linear backward");
   return TAW_OK;
 }

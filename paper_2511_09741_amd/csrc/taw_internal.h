@@ -13,6 +13,16 @@ enum { GEMM_NT = 0, GEMM_NN = 1, GEMM_TN = 2 };
 
 inline size_t dt_size(int dt) { return dt == DT_BF16 ? 2 : 4; }
 
+// Raises a kernel's dynamic-LDS limit to `bytes` the first time the enclosing function (or template
+// instantiation) runs, and returns from it with the HIP error code if that failed.  The limit is a
+// property of the kernel, not of a launch: a function-local static is initialised exactly once, and
+// thread-safely.  `bytes` must be the largest size that launcher ever asks for.
+#define TAW_SET_LDS_LIMIT_ONCE(kernel, bytes)                                                                                  \
+  do {                                                                                                                       \
+    static const int taw_lds_rc_ = (int)hipFuncSetAttribute((const void*)(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)(bytes)); \
+    if (taw_lds_rc_) return taw_lds_rc_;                                                                                     \
+  } while (0)
+
 // ---- bandwidth-bound kernels (kernels_bw.hip) ------------------------------------------------
 // Largest H the RMSNorm kernels hold in registers: H * sizeof(elem) <= 16 KiB when H is a multiple
 // of the 16-byte vector width, else H <= 1024.

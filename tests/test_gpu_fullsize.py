@@ -123,7 +123,7 @@ def test_c3_attention_sampled(taw):
     taw.taw_op_attn_fwd(BF, B, S, nh, d, qkv, o, lse, taw.TAW_IMPL_MFMA)
     dqkv = torch.empty_like(qkv)
     scratch = torch.empty(taw.taw_op_attn_bwd_scratch_floats(B, S, nh), dtype=torch.float32, device="cuda")
-    taw.taw_op_attn_bwd(BF, B, S, nh, d, qkv, o, dO, lse, dqkv, scratch, taw.TAW_IMPL_MFMA)
+    taw.taw_op_attn_bwd(BF, B, S, nh, d, qkv, o, dO, lse, dqkv, scratch, None, taw.TAW_IMPL_MFMA)
     torch.cuda.synchronize()
     rows = np.array([0, 1, 63, 64, 255, 256, 257, 8191, 8192, 20000, 32767 - 256, 32767])
     t0 = S - 300

@@ -17,14 +17,14 @@ def test_c1_fp32_tiny_layer(taw, seed):
 def test_c1_shapes_with_peaked_attention_and_nontrivial_gains(taw):
     """At sigma_w = 0.02 the scores are nearly flat; sigma_w = 0.5 makes the softmax peaked, and
     gains away from 1 make a dropped gamma visible."""
-    U.check_layer(taw, I.CONFIGS["C1"], seed=3, sigma_w=0.5, gamma_jitter=0.3, tol=2e-4)
+    U.check_layer(taw, I.CONFIGS["C1"], seed=3, sigma_w=0.5, gamma_jitter=0.3)
 
 
 @pytest.mark.parametrize("B,S,H,nh,I_", [(2, 37, 48, 3, 40), (1, 1, 32, 2, 24), (3, 65, 64, 4, 100), (1, 200, 30, 3, 50)])
 def test_fp32_ragged_shapes(taw, B, S, H, nh, I_):
     """Generic kernels on shapes that are no multiple of any tile or vector width (S=1 included)."""
     cfg = I.LayerConfig("ragged", I.F32, B, S, H, nh, H // nh, I_)
-    U.check_layer(taw, cfg, seed=4, sigma_w=0.3, gamma_jitter=0.2, tol=2e-4)
+    U.check_layer(taw, cfg, seed=4, sigma_w=0.3, gamma_jitter=0.2)
 
 
 def test_bf16_storage_on_generic_kernels(taw):

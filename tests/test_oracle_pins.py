@@ -325,6 +325,39 @@ def test_sampled_rows_agree_with_full_forward():
     assert np.max(np.abs(yr - y[0, rows])) < 1e-12
 
 
+@pytest.mark.parametrize("t0", [0, 1, 20, 32])
+def test_backward_tail_agrees_with_full_backward(t0):
+    """layer_bwd_tail (the closed sub-problem at the rows t >= t0, used for full-size parity of the
+    layer's backward) against the complete layer_fwd + layer_bwd, and against central finite
+    differences of the loss <dy, y> in x at those rows (which no oracle code path shares)."""
+    rng = np.random.default_rng(23 + t0)
+    h, nh, i, s = 32, 4, 40, 33
+    W = tiny_weights(rng, h, i)
+    x = rng.standard_normal((1, s, h))
+    dy = rng.standard_normal((1, s, h))
+    _, cache = O.layer_fwd(W, x, nh)
+    dx, _ = O.layer_bwd(W, cache, dy)
+    tail = O.layer_bwd_tail(W, x[0], dy[0], t0, nh)
+    assert tail.shape == (s - t0, h)
+    assert np.max(np.abs(tail - dx[0, t0:])) < 1e-11
+    eps = 1e-5
+    for _ in range(3):
+        v = np.zeros_like(x)
+        v[0, t0:] = rng.standard_normal((s - t0, h))
+        lp = float(np.sum(O.layer_fwd(W, x + eps * v, nh)[0] * dy))
+        lm = float(np.sum(O.layer_fwd(W, x - eps * v, nh)[0] * dy))
+        ana = float(np.sum(tail * v[0, t0:]))
+        assert abs((lp - lm) / (2 * eps) - ana) <= 1e-7 * max(1.0, abs(ana))
+
+
+def test_backward_tail_catches_a_dropped_key_contribution(monkeypatch):
+    """Planted mistake: if the tail form ignored the rotary backward, the comparison above must fail."""
+    orig = O.rope_apply
+    monkeypatch.setattr(O, "rope_apply", lambda z, phi, inverse=False: z if inverse else orig(z, phi))
+    with pytest.raises(AssertionError):
+        test_backward_tail_agrees_with_full_backward(20)
+
+
 # ------------------------------------------------------------------ independent library implementation
 def test_against_torch_fp64_autograd():
     """Same block written with torch CPU fp64 ops (complex-number RoPE, library SDPA, autograd

@@ -2,6 +2,7 @@
 (tests/golden/paper_schedule_examples.txt), the mapping formula, the closed forms of the
 Theoretical Analysis, and structural invariants of the step table."""
 import itertools
+import os
 
 import pytest
 
@@ -10,17 +11,40 @@ import paper_2511_09741_amd.binding as taw
 FWD, BWD, IDLE = 1, 2, 0
 
 
+def _golden():
+    """(key, value, citation) of every line of tests/golden/paper_schedule_examples.txt"""
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "paper_schedule_examples.txt")
+    out = []
+    with open(path) as f:
+        for line in f:
+            line = line.strip()
+            if not line or line.startswith("#"):
+                continue
+            lhs, cite = line.split(";", 1)
+            key, val = lhs.split("=")
+            out.append((key.split(), int(val), cite.strip()))
+    return out
+
+
 def test_worked_example_of_the_paper():
+    """Every value the paper states for its six-device example (two groups of three, six layers), read from the
+    golden file, against the schedule model."""
     P, D, L = 6, 2, 6
-    assert [taw.taw_sched_owner(P, D, L, j)[0] for j in (0, 1, 4, 5)] == [0, 3, 2, 5]
-    s = taw.taw_sched_step(P, D, L, 0, 4)
-    assert s["phase"] == FWD and s["layer"] == 4 and s["master"] == 2 and s["prefetch_from"] == 5
-    assert taw.taw_sched_step(P, D, L, 0, 0)["prefetch_from"] == 3
-    s = taw.taw_sched_step(P, D, L, 1, 1)
-    assert s["phase"] == FWD and s["layer"] == 0 and s["master"] == 3
-    s = taw.taw_sched_step(P, D, L, 0, 6)
-    assert s["phase"] == BWD and s["layer"] == 5 and s["master"] == 2
-    assert taw.taw_sched_update_step(P, D, L, 5) == 7
+    lines = _golden()
+    assert len(lines) >= 16
+    kinds = set()
+    for key, val, cite in lines:
+        kinds.add(key[0])
+        if key[0] == "owner":
+            got = taw.taw_sched_owner(P, D, L, int(key[1]))[0]
+        elif key[0] == "step":
+            got = taw.taw_sched_step(P, D, L, int(key[1][1:]), int(key[2][1:]))[key[3]]
+        elif key[0] == "update":
+            got = taw.taw_sched_update_step(P, D, L, int(key[1]))
+        else:
+            raise AssertionError(f"unknown key {key}")
+        assert got == val, (key, got, val, cite)
+    assert kinds == {"owner", "step", "update"}
 
 
 @pytest.mark.parametrize("P,D", [(6, 2), (8, 1), (24, 3), (16, 4), (4, 4)])
