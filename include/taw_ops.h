@@ -87,7 +87,8 @@ int taw_op_qkv_rope(int32_t dtype, int32_t B, int32_t S, int32_t n_heads, int32_
 /* Backward of a linear y [T, N] = x [T, K] W[N, K]^T given dy, as taw_layer_bwd runs it:
  *   dx [T, K] = dy W              (storage type dtype)
  *   G  [N, K] (=|+=) dy^T x       (fp32; += when accumulate != 0)
- * On the MFMA path the two products share one grid when T and N are multiples of 32. */
+ * On the MFMA path the two products share one grid when T and N are multiples of 32.
+ * A dimension of 0 makes the call a no-op (G is left as it is). */
 int taw_op_linear_bwd(int32_t dtype, int64_t T, int64_t N, int64_t K, const void* dy, const void* W, const void* x,
                       void* dx, float* G, int32_t accumulate, int32_t impl, void* stream);
 

@@ -527,15 +527,11 @@ extern "C" int taw_op_linear_bwd(int32_t dtype, int64_t T, int64_t N, int64_t K,
   if (rc) return rc;
   if (T < 0 || N < 0 || K < 0) return fail(TAW_ERR_SHAPE, "negative dimension");
   if (impl < TAW_IMPL_AUTO || impl > TAW_IMPL_MFMA) return fail(TAW_ERR_SHAPE, "unknown impl %d", impl);
-  if (K == 0 || (T == 0 && N == 0)) return TAW_OK;
-  if (T > 0) { TAW_REQUIRE_PTR(dx); TAW_REQUIRE_ALIGNED(dx); }
-  if (N > 0) { TAW_REQUIRE_PTR(G); TAW_REQUIRE_ALIGNED(G); }
-  if (T > 0 && N > 0) {
-    TAW_REQUIRE_PTR(dy); TAW_REQUIRE_PTR(W); TAW_REQUIRE_PTR(x);
-    TAW_REQUIRE_ALIGNED(dy); TAW_REQUIRE_ALIGNED(W); TAW_REQUIRE_ALIGNED(x);
-  }
+  if (T == 0 || N == 0 || K == 0) return TAW_OK;
+  TAW_REQUIRE_PTR(dy); TAW_REQUIRE_PTR(W); TAW_REQUIRE_PTR(x); TAW_REQUIRE_PTR(dx); TAW_REQUIRE_PTR(G);
+  TAW_REQUIRE_ALIGNED(dy); TAW_REQUIRE_ALIGNED(W); TAW_REQUIRE_ALIGNED(x); TAW_REQUIRE_ALIGNED(dx); TAW_REQUIRE_ALIGNED(G);
   const hipStream_t st = (hipStream_t)stream;
-  const bool can = T > 0 && N > 0 && gemm_mfma_supported(dtype, GEMM_NN, T, K, N, N, K, K, dtype, 0) &&
+  const bool can = gemm_mfma_supported(dtype, GEMM_NN, T, K, N, N, K, K, dtype, 0) &&
                    gemm_mfma_supported(dtype, GEMM_TN, N, K, T, N, K, K, DT_F32, 0);
   if (impl == TAW_IMPL_MFMA && !can) return fail(TAW_ERR_UNSUPPORTED, "MFMA GEMMs need bf16 and N, K multiples of 8");
   Plan p;

@@ -184,6 +184,26 @@ def test_op_validation(lib):
     with pytest.raises(taw.TawError) as e:
         taw.taw_op_rope(taw.TAW_F32, 1, 16, 24, 16, ok, 24, ok)
     assert e.value.status == taw.TAW_ERR_SHAPE           # ncols not a multiple of head_dim
+    # the paired backward of a linear, the rotated qkv projection, the rotary argument of the attention backward
+    with pytest.raises(taw.TawError) as e:
+        taw.taw_op_linear_bwd(taw.TAW_F32, 8, 8, 8, ok, ok, ok, ok, ok, 0, taw.TAW_IMPL_MFMA)
+    assert e.value.status == taw.TAW_ERR_UNSUPPORTED     # fp32 has no MFMA kernel
+    with pytest.raises(taw.TawError) as e:
+        taw.taw_op_linear_bwd(taw.TAW_BF16, 8, 8, 8, ok, None, ok, ok, ok)
+    assert e.value.status == taw.TAW_ERR_NULL
+    with pytest.raises(taw.TawError) as e:
+        taw.taw_op_linear_bwd(taw.TAW_BF16, 8, -1, 8, ok, ok, ok, ok, ok)
+    assert e.value.status == taw.TAW_ERR_SHAPE
+    taw.taw_op_linear_bwd(taw.TAW_BF16, 8, 8, 0, None, None, None, None, None)     # K = 0: both outputs are empty
+    with pytest.raises(taw.TawError) as e:
+        taw.taw_op_qkv_rope(taw.TAW_BF16, 1, 16, 2, 15, ok, ok, ok, ok)
+    assert e.value.status == taw.TAW_ERR_SHAPE           # odd head_dim
+    with pytest.raises(taw.TawError) as e:
+        taw.taw_op_qkv_rope(taw.TAW_BF16, 1, 16, 2, 16, ok, ok, ok, None)
+    assert e.value.status == taw.TAW_ERR_NULL            # the table is required here
+    with pytest.raises(taw.TawError) as e:
+        taw.taw_op_attn_bwd(taw.TAW_BF16, 1, 16, 2, 128, ok, ok, ok, ok, ok, ok, ok + 4)
+    assert e.value.status == taw.TAW_ERR_ALIGN           # rope_table given but misaligned
 
 
 def test_missing_library_fails_loudly(monkeypatch, tmp_path):
