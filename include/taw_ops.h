@@ -48,6 +48,19 @@ int taw_op_rmsnorm_bwd(int32_t dtype, int64_t T, int32_t H, const void* dout, co
                        const void* gamma, const void* dres, void* dz, float* dgamma, int32_t accumulate,
                        float* scratch, void* stream);
 
+/* taw_op_rmsnorm_bwd for callers that cannot allocate device memory or pass a workspace (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc): the same kernels, with the partial-sum scratch
+ * in a static device array inside the library (16 MiB, held on every GPU the library runs on until the process
+ * ends).  Same arguments as taw_op_rmsnorm_bwd without `scratch`; same results, bit for bit.
+ *   limit       H <= 8192 (TAW_ERR_WORKSPACE beyond it: use taw_op_rmsnorm_bwd with a caller-owned scratch)
+ *   allocation  none: no hipMalloc / hipFree, no allocating library call
+ *   sharing     every call on a GPU uses that GPU's one array; the call clears nothing because every scratch row it
+ *               reads it has written first; two calls that overlap in time on one GPU (different streams) race on
+ *               the array and must be ordered by the caller */
+int taw_op_rmsnorm_bwd_static(int32_t dtype, int64_t T, int32_t H, const void* dout, const void* z, const float* r,
+                              const void* gamma, const void* dres, void* dz, float* dgamma, int32_t accumulate,
+                              void* stream);
+
 /* Rotary embedding in place on columns [0, ncols) of z [B*S, ld]; ncols a multiple of head_dim.
  * Pair (2i, 2i+1) of each head at position p turns by p*theta^(-2i/d); inverse != 0 turns back
  * (the backward map). */

@@ -74,6 +74,7 @@ _SIGS = {
     "taw_op_rmsnorm_bwd_scratch_floats": (_sz, [_i32]),
     "taw_op_attn_bwd_scratch_floats": (_sz, [_i32, _i32, _i32]),
     "taw_op_rmsnorm_bwd": (C.c_int, [_i32, _i64, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _vp, _vp]),
+    "taw_op_rmsnorm_bwd_static": (C.c_int, [_i32, _i64, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _vp]),
     "taw_op_rope": (C.c_int, [_i32, _i32, _i32, _i32, _i32, _vp, _i64, _vp, _i32, _vp]),
     "taw_op_swiglu_fwd": (C.c_int, [_i32, _i64, _i32, _vp, _vp, _vp]),
     "taw_op_swiglu_bwd": (C.c_int, [_i32, _i64, _i32, _vp, _vp, _vp, _vp]),
@@ -249,6 +250,11 @@ def taw_op_rmsnorm_bwd_scratch_floats(H) -> int:
 def taw_op_rmsnorm_bwd(dtype, T, H, dout, z, r, gamma, dres, dz, dgamma, accumulate, scratch, stream=None):
     _check(load().taw_op_rmsnorm_bwd(dtype, T, H, _p(dout), _p(z), _p(r), _p(gamma), _p(dres), _p(dz), _p(dgamma), accumulate,
                                      _p(scratch), _stream(stream)))
+
+
+def taw_op_rmsnorm_bwd_static(dtype, T, H, dout, z, r, gamma, dres, dz, dgamma, accumulate, stream=None):
+    _check(load().taw_op_rmsnorm_bwd_static(dtype, T, H, _p(dout), _p(z), _p(r), _p(gamma), _p(dres), _p(dz), _p(dgamma), accumulate,
+                                            _stream(stream)))
 
 
 def taw_op_rope(dtype, B, S, ncols, head_dim, z, ld, rope_table, inverse=0, stream=None):

@@ -6,6 +6,7 @@
 #include <cstring>
 #include <cstdarg>
 #include <cmath>
+#include <mutex>
 
 #include "../../include/taw.h"
 #include "../../include/taw_ops.h"
@@ -411,6 +412,56 @@ extern "C" int taw_op_rmsnorm_bwd(int32_t dtype, int64_t T, int32_t H, const voi
   TAW_REQUIRE_ALIGNED(dout); TAW_REQUIRE_ALIGNED(z); TAW_REQUIRE_ALIGNED(gamma); TAW_REQUIRE_ALIGNED(dz); TAW_REQUIRE_ALIGNED(scratch);
   if (dres) TAW_REQUIRE_ALIGNED(dres);
   TAW_LAUNCH(launch_rmsnorm_bwd(dtype, T, H, dout, z, r, gamma, dres, dz, dgamma, accumulate, scratch, (hipStream_t)stream), "rmsnorm_bwd");
+  return TAW_OK;
+}
+
+// ---- the same operation for callers that cannot allocate: the partial-sum scratch lives in a static device array.
+// The array's name is only a host-side handle; its device address is looked up once per device (with that device
+// current) and kept, and that address is what the launcher and its kernels get.
+static constexpr int kStaticNormMaxH = 8192;
+static __device__ __align__(256) float g_norm_scratch[(size_t)512 * kStaticNormMaxH];      // 16 MiB on every GPU the library runs on
+static constexpr int kMaxDevices = 64;
+static float* g_norm_scratch_ptr[kMaxDevices];
+static std::mutex g_norm_scratch_mu;
+
+static int norm_scratch_for_current_device(float** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return hip_fail((int)e, "hipGetDevice");
+  if (dev < 0 || dev >= kMaxDevices) return fail(TAW_ERR_UNSUPPORTED, "device ordinal %d is beyond the %d this entry point keeps a scratch address for", dev, kMaxDevices);
+  std::lock_guard<std::mutex> lock(g_norm_scratch_mu);
+  if (!g_norm_scratch_ptr[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(g_norm_scratch));
+    if (e != hipSuccess) return hip_fail((int)e, "hipGetSymbolAddress(static RMSNorm scratch)");
+    if (!p) return fail(TAW_ERR_HIP, "hipGetSymbolAddress returned a null address for the static RMSNorm scratch");
+    g_norm_scratch_ptr[dev] = static_cast<float*>(p);
+  }
+  *out = g_norm_scratch_ptr[dev];
+  return TAW_OK;
+}
+
+extern "C" int taw_op_rmsnorm_bwd_static(int32_t dtype, int64_t T, int32_t H, const void* dout, const void* z, const float* r,
+                                         const void* gamma, const void* dres, void* dz, float* dgamma, int32_t accumulate, void* stream) {
+  int rc = check_dtype(dtype);
+  if (rc) return rc;
+  if (T < 0 || H <= 0) return fail(TAW_ERR_SHAPE, "bad shape T=%lld H=%d", (long long)T, H);
+  if (H > kStaticNormMaxH)
+    return fail(TAW_ERR_WORKSPACE, "H=%d exceeds the %d columns the static scratch of taw_op_rmsnorm_bwd_static holds; use taw_op_rmsnorm_bwd with a caller-owned scratch",
+                H, kStaticNormMaxH);
+  if (!rmsnorm_supported(dtype, H)) return fail(TAW_ERR_UNSUPPORTED, "H=%d too wide for the RMSNorm kernels", H);
+  static_assert((size_t)512 * kStaticNormMaxH * sizeof(float) == sizeof(g_norm_scratch), "scratch size");
+  if ((size_t)rmsnorm_bwd_partial_rows() * (size_t)H * sizeof(float) > sizeof(g_norm_scratch))
+    return fail(TAW_ERR_WORKSPACE, "static scratch too small for H=%d", H);
+  if (T == 0) return TAW_OK;
+  TAW_REQUIRE_PTR(dout); TAW_REQUIRE_PTR(z); TAW_REQUIRE_PTR(r); TAW_REQUIRE_PTR(gamma); TAW_REQUIRE_PTR(dz); TAW_REQUIRE_PTR(dgamma);
+  TAW_REQUIRE_ALIGNED(dout); TAW_REQUIRE_ALIGNED(z); TAW_REQUIRE_ALIGNED(gamma); TAW_REQUIRE_ALIGNED(dz);
+  if (dres) TAW_REQUIRE_ALIGNED(dres);
+  float* scratch = nullptr;
+  rc = norm_scratch_for_current_device(&scratch);
+  if (rc) return rc;
+  // every partial row the column-sum pass reads is written by this call's first kernel: nothing has to start at zero
+  TAW_LAUNCH(launch_rmsnorm_bwd(dtype, T, H, dout, z, r, gamma, dres, dz, dgamma, accumulate, scratch, (hipStream_t)stream), "rmsnorm_bwd (static scratch)");
   return TAW_OK;
 }
 
