@@ -60,6 +60,10 @@ typedef enum { TAW_F32 = 0, TAW_BF16 = 1 } taw_dtype;
                              layer's intermediates from x inside the workspace, which is larger by
                              what ctx would have held.  Same results, about 4/3 of the arithmetic. */
 
+#define TAW_ATTN_BWD_FUSED 4u /* taw_layer_bwd runs the attention backward as one kernel that forms the scores once and
+                                 keeps dQ partial sums in private fp32 slots (the workspace grows by those slots), instead of
+                                 the default pair of kernels (dK/dV, then dQ) that each recompute the scores */
+
 /* One decoder layer and the micro-batch it is applied to (B, S, H as in the paper's Table 1). */
 typedef struct {
   int32_t dtype;      /* taw_dtype of activations and weights; the gradient shard is always fp32 */
@@ -71,7 +75,7 @@ typedef struct {
   int32_t I;          /* SwiGLU intermediate width */
   float rope_theta;   /* rotary base, 10000 for LLaMA-2 */
   float rms_eps;      /* added to the mean of squares inside the square root */
-  uint32_t flags;     /* TAW_ACCUMULATE | TAW_RECOMPUTE */
+  uint32_t flags;     /* TAW_ACCUMULATE | TAW_RECOMPUTE | TAW_ATTN_BWD_FUSED */
 } taw_layer_desc;
 
 /* Element offsets of the sub-tensors inside the flat weight chunk W_j (the unit that is moved

@@ -1,0 +1,55 @@
+/* taw_diag.h -- measurement probes of the library: what the part sustains, against which the kernels'
+ * rates are read.  Not part of the hot path: every call here runs a short synthetic kernel, WAITS for it
+ * (the only calls of the library that synchronise with the host) and returns the measured figures in host
+ * memory.  bench.py --workload diag prints them; profiles/mfma_ceiling.md records a run.
+ *
+ * Why they exist.  The layer's roofline is the dense bf16 matrix rate (Experimental Setup of the paper trains in
+ * 16-bit precision; the target of this build is quoted against the 2.5 PFLOP/s figure).  On real operands that
+ * rate is not reachable: the part lowers its clock under the power the matrix cores draw.  These probes put the
+ * sustained figures on record: a loop of nothing but MFMAs, the same loop with the LDS fragment reads and the
+ * global->LDS loads a GEMM tile needs, the LDS read rate, and the rate of fp32 atomic adds (which decides
+ * whether an attention backward that accumulates dQ with atomics can pay).
+ *
+ * Same conventions as taw.h: int status, no exceptions, device pointers 16-byte aligned, host pointers for results. */
+#ifndef TAW_DIAG_H
+#define TAW_DIAG_H
+
+#include "taw.h"
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+  TAW_DIAG_MFMA_RANDOM = 0,       /* v_mfma_f32_32x32x16_bf16 back to back, operands in registers, random bf16 values */
+  TAW_DIAG_MFMA_ZERO = 1,         /* the same on all-zero operands (no switching activity: the clock stays up) */
+  TAW_DIAG_MFMA_LDS = 2,          /* + one LDS fragment read (ds_read_b128) per two MFMAs, the ratio of a 128x128 wavefront tile */
+  TAW_DIAG_MFMA_LDS_LOADS = 3     /* + one direct global->LDS load (16 bytes per lane) per four MFMAs, the ratio of a 256x256x64 tile step */
+};
+
+typedef struct {
+  double tflops;      /* 2 * 32 * 32 * 16 flops per MFMA, all 256 compute units x 4 wavefronts */
+  double clock_ghz;   /* shader clock inside the loop: core-clock ticks over wall-clock ticks */
+  double mfma_busy;   /* 32 cycles per MFMA over the cycles the loop took: 1.0 = the matrix pipe never idles */
+  double ms;          /* duration of the launch */
+} taw_diag_rate;
+
+/* kind: TAW_DIAG_MFMA_*.  iters: loop trips of 16 MFMAs per wavefront (>= 1; 20000 gives about 10 ms).
+ * src / src_bytes: a device buffer the loads of TAW_DIAG_MFMA_LDS_LOADS stream from (>= 1 MiB, a multiple of
+ * 64 KiB; ignored by the other kinds, may be NULL there).  Synchronises with the host. */
+int taw_diag_mfma_loop(int32_t kind, int32_t iters, const void* src, size_t src_bytes, taw_diag_rate* out);
+
+/* LDS read rate of one compute unit, bytes per core clock: instr 0 = ds_read_b128, 1 = ds_read_b64,
+ * 2 = ds_read_b64_tr_b16; waves = 4 or 8 wavefronts per compute unit, conflict-free addresses. */
+int taw_diag_lds_read_rate(int32_t instr, int32_t waves, double* bytes_per_clock_per_cu, double* clock_ghz);
+
+/* Rate of dQ-tile updates in the access pattern of a key-stationary attention backward: every workgroup walks down
+ * the query rows of its head from its key block's diagonal on and updates a [32 x 128] fp32 tile per step (rows of
+ * 128 contiguous bytes per half wavefront).  mode 0: no-return fp32 atomic adds; 1: plain stores; 2: load, add, store
+ * (what a private slot allows).  buf: S * n_heads * 128 floats (overwritten).  *updates_per_s counts 4-byte elements. */
+int taw_diag_dq_update_rate(float* buf, int32_t S, int32_t n_heads, int32_t mode, double* updates_per_s, double* ms);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TAW_DIAG_H */

@@ -767,6 +767,385 @@ attn_bwd_dq_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dO
   store_rows_T(dq, scale, stage, dqout, ld, q0w, S, lane);
 }
 
+// =============================================================================== backward: dK, dV and dQ in one kernel
+// Five matrix products per (query block, key block) pair instead of the seven of the split pair above: S and dP are formed
+// once, by the key-stationary side, and dQ is produced from the same dS.  The obstacle is the register layout: the
+// accumulators of S and dP give a lane one KEY column, and the matrix cores contract over registers, never over lanes, so
+// dQ[q][d] = sum_kv dS[q][kv] K[kv][d] cannot be fed from them.  Here dS crosses the workgroup through LDS:
+//   phase 1 (every wavefront, its own 32 keys, one block of 32 query rows): S, P, dP, dS as in the dK/dV kernel above;
+//           dV^T += dO^T P, dK^T += Q^T dS; dS (bf16) is written to an exchange tile Ex^T[256 keys][32 rows];
+//   phase 2 (one block later, after the workgroup barrier that publishes Ex^T): dQ[32 rows][128] = dS[32][256] K[256][128],
+//           split by OUTPUT: four wavefronts take one 32-column tile each and contract over all 256 keys (operands: dS from
+//           Ex^T and K from a copy of the key tile in LDS, both by transposing reads); the two wavefronts of a SIMD take
+//           turns, so every SIMD sees 80 MFMAs per block.
+// Where the dQ tile goes decides the kernel's speed, and on this part neither way beats the split pair, which is why that
+// pair stays the default (S = 32768, 32 heads: split 26.7 ms; this kernel 24.1 ms when it drops the dQ tiles, 27.2 ms
+// with atomics, 30.4 ms with slots):
+//   kDqAtomic  fp32 atomic adds into one dQ buffer.  The atomic units retire 0.34 T adds/s, and a 256-key workgroup
+//              issues S^2/4 adds per head: 25.4 ms for the adds alone at that size.
+//   kDqSlots   a deterministic two-level split over key blocks without atomics: the key blocks of a (batch, head) are dealt
+//              to Ns WORKERS (one workgroup each, processing its key blocks one after the other); worker s owns a private
+//              fp32 copy ("slot") of dQ and adds each tile into it with plain loads and stores (nobody else touches that
+//              slot, and one workgroup's own accesses are ordered); a last pass sums the slots, scales, rotates back and
+//              rounds to bf16.  A worker's first key block stores instead of adding, and slot s is never read above the
+//              first row it wrote, so nothing has to be cleared.  Every tile pair moves 32 KB through HBM this way
+//              (69 GB at that size), which costs more than recomputing the scores does.
+constexpr int kDqSlots = 0, kDqAtomic = 1;
+constexpr int kFBQ = 32;                               // query rows per block
+constexpr int kFStage = 2 * 8192 + 256;                // Q tile [32][128] | dO tile | lse[32] | D[32]
+constexpr int kFStages = 3;
+constexpr int kFOffK = 0;                              // key tile [256][128] bf16
+constexpr int kFOffEx = 65536;                         // two exchange tiles [256][32] bf16
+constexpr int kFOffRing = kFOffEx + 2 * 16384;
+constexpr size_t kFusedLds = kFOffRing + kFStages * kFStage;     // 148224 bytes
+static_assert(kFusedLds <= 160 * 1024, "LDS budget");
+static_assert(kFusedLds >= 8 * 32 * 136 * sizeof(bf16_t), "output staging area");
+
+// one-KiB piece `wave` (rows 4 wave .. 4 wave + 3) of a [32][128] tile, as tile_dma does for [64][128]
+__device__ __forceinline__ void tile32_dma(uint64_t base, unsigned ld_bytes, int row0, int limit, unsigned lds_tile, int lane, int wave) {
+  const int r = 4 * wave + (lane >> 4);
+  const int c = swz(r, lane & 15);
+  int rg = row0 + r;
+  rg = rg < limit ? rg : limit - 1;
+  lds_dma16(base, (unsigned)rg * ld_bytes + c * 16, lds_tile + wave * 1024);
+}
+
+// Key blocks of one (batch, head) dealt to Ns workers in snake order: round r gives worker s the block r Ns + s (r even)
+// or r Ns + Ns - 1 - s (r odd), so every worker gets the same number of (query block, key block) pairs when the
+// number of rounds is even.  Worker s starts at block s.
+__device__ __forceinline__ int worker_block(int r, int s, int Ns) { return r * Ns + ((r & 1) ? Ns - 1 - s : s); }
+
+template <int DQ>
+__global__ void __launch_bounds__(kThreads8, 1)
+attn_bwd_fused_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dO, const float* __restrict__ prep,
+                      bf16_t* __restrict__ dqkv, float* __restrict__ dq_slots, int B, int S, int Sp, int nh, float scale,
+                      const float* __restrict__ rope, int Ns, int nworkers) {
+  extern __shared__ __attribute__((aligned(256))) unsigned char lds_raw[];
+  const lds_u8_t* L = (const lds_u8_t*)lds_raw;
+  const unsigned lds0 = (unsigned)(size_t)L;
+  const int tid = threadIdx.x, lane = tid & 63, hh = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  LaneAddr la;
+  la.init(lane);
+  const int dtile = wave & 3;                            // phase 2: this wavefront's 32 columns of dQ
+
+  // ---- which (batch, head) and which key blocks
+  int wid = blockIdx.x;
+  if ((nworkers & 7) == 0) wid = (wid & 7) * (nworkers >> 3) + (wid >> 3);       // workers of one head share an XCD's L2
+  const int nkt = (S + 255) / 256;
+  int bh, slot;
+  if (DQ == kDqSlots) { bh = wid / Ns; slot = wid % Ns; }
+  else { bh = blockIdx.x % (B * nh); slot = 0; }
+  const int b = bh / nh, h = bh % nh;
+  const int64_t H = (int64_t)nh * D, ld = 3 * H;
+  const bf16_t* qbase = qkv + (int64_t)b * S * ld + (int64_t)h * D;
+  const bf16_t* kbase = qbase + H;
+  const bf16_t* vbase = qbase + 2 * H;
+  const uint64_t qb64 = (uint64_t)qbase, k64 = (uint64_t)kbase, do64 = (uint64_t)(dO + (int64_t)b * S * H + (int64_t)h * D);
+  const uint64_t l64 = (uint64_t)(prep + ((int64_t)b * nh + h) * Sp);
+  const unsigned d_off = (unsigned)((int64_t)B * nh * Sp * 4);                   // D follows the scaled lse in prep
+  const unsigned ldb = (unsigned)(ld * 2), ldob = (unsigned)(H * 2);
+  const float c = scale * kLog2e;
+  // dQ tile of this wavefront in its slot (or in the one atomic buffer), row 0 of the (batch, head): wavefront-uniform
+  float* dq_tile = dq_slots + (int64_t)slot * ((int64_t)B * S * H) + (int64_t)b * S * H + (int64_t)h * D + dtile * 32;
+  const unsigned Hb = (unsigned)(H * 4);
+
+  for (int round = 0;; ++round) {
+    int kt;
+    if (DQ == kDqSlots) { kt = worker_block(round, slot, Ns); if (kt >= nkt) break; }
+    else { if (round) break; kt = blockIdx.x / (B * nh); }
+    const bool first = DQ == kDqSlots && round == 0;     // store, do not add: the slot holds nothing yet
+    const int kv0 = kt * 256, kv0w = kv0 + wave * 32;
+    const int jb = kv0 / kFBQ, je = (S + kFBQ - 1) / kFBQ, nblk = je - jb;
+
+    __syncthreads();                                     // everybody is done with the previous key block's LDS
+    // key tile -> LDS (8 pieces of 4 rows per wavefront), then the first two query blocks
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int j = wave + 8 * i;
+      const int r = 4 * j + (lane >> 4);
+      const int cc = swz(r, lane & 15);
+      int rg = kv0 + r;
+      rg = rg < S ? rg : S - 1;
+      lds_dma16(k64, (unsigned)rg * ldb + cc * 16, lds0 + kFOffK + j * 1024);
+    }
+    auto issue = [&](int t) {
+      const unsigned st = lds0 + kFOffRing + (t % kFStages) * kFStage;
+      const int row0 = (jb + t) * kFBQ;
+      tile32_dma(qb64, ldb, row0, S, st, lane, wave);
+      tile32_dma(do64, ldob, row0, S, st + 8192, lane, wave);
+      if (wave == 0) lds_dma4(l64, (lane < 32 ? 0u : d_off) + (unsigned)(row0 + (lane & 31)) * 4u, st + 16384);
+    };
+    for (int t = 0; t < 2 && t < nblk; ++t) issue(t);
+
+    // V rows of this wavefront's keys stay in registers as B operands; its K rows are read from the key tile in LDS
+    // (which phase 2 needs there anyway): the registers they would take are what phase 2 accumulates in
+    bf16x8_t vf[8];
+    {
+      int row = kv0w + (lane & 31);
+      if (row >= S) row = S - 1;
+#pragma unroll
+      for (int ks = 0; ks < 8; ++ks) vf[ks] = *reinterpret_cast<const bf16x8_t*>(vbase + (int64_t)row * ld + 16 * ks + 8 * hh);
+    }
+    f32x16_t dk[4], dv[4];
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) { dk[dt][r] = 0.f; dv[dt][r] = 0.f; }
+    const int kvi = kv0w + (lane & 31);
+    const unsigned knat_t = la.nat + lds0 + kFOffK + wave * 8192;
+
+    // ---- phase 2 in three parts, so that the slot values a wavefront adds to are requested a whole phase 1 before they are
+    // needed (they come from HBM).  Lane constants are made from an opaque copy of the lane number where they are used, so
+    // that none of them stays in a register through phase 1.
+    // accumulator register r of a lane is dQ[qrow0 + 8 (r / 4) + 4 (lane >> 5) + r % 4][lane & 31]: a wavefront-uniform row
+    // base (scalar arithmetic) plus one 32-bit lane offset
+    auto dq_at = [&](int tq, int ln, int r) {
+      char* tile = reinterpret_cast<char*>(dq_tile + (int64_t)((jb + tq) * kFBQ) * H);
+      const unsigned voff = (unsigned)(4 * (ln >> 5)) * Hb + (unsigned)(ln & 31) * 4u;
+      return reinterpret_cast<float*>(tile + (size_t)(8 * (r >> 2) + (r & 3)) * Hb + (size_t)voff);
+    };
+    // (a) what the slot holds for query block tq (zeros where there is nothing to add to)
+    auto dq_fetch = [&](int tq, f32x16_t& acc) {
+      int ln = lane;
+      asm volatile("" : "+v"(ln));
+      const int qrow0 = (jb + tq) * kFBQ;
+      if (DQ != kDqSlots || first) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+      } else if (qrow0 + kFBQ <= S) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[r] = __hip_atomic_load(dq_at(tq, ln, r), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      } else {                                           // the last block of a sequence that is no multiple of 32
+        const int qlane = qrow0 + 4 * (ln >> 5);
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+          acc[r] = qlane + 8 * (r >> 2) + (r & 3) < S ? __hip_atomic_load(dq_at(tq, ln, r), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0.f;
+      }
+    };
+    // (b) acc += dS K over the keys up to the block's last row: two independent accumulation chains (even and odd key steps)
+    auto dq_mfma = [&](int tq, f32x16_t& acc) {
+      int ln = lane;
+      asm volatile("" : "+v"(ln));
+      unsigned ex_tr, k_tr;
+      {
+        const int blk = ln >> 4, i = ln & 15, hb = blk >> 1;
+        const int rl = 4 * hb + (i >> 2), q = 16 * (blk & 1) + 4 * (i & 3);
+        ex_tr = rl * 64 + (((q >> 3) ^ ((rl >> 2) & 3)) << 4) + (q & 7) * 2;                 // exchange tile: 64-byte rows, chunks swizzled by (row >> 2) & 3
+        k_tr = (rl * 256 + (swz(rl, q >> 3) << 4) + (q & 7) * 2) ^ ((unsigned)dtile << 6);   // key tile: as LaneAddr::tr, at this wavefront's 32 columns
+      }
+      const int qrow0 = (jb + tq) * kFBQ;
+      int nks = (qrow0 + kFBQ - kv0 + 15) >> 4;          // 16-key steps that hold a visible key: even, wavefront-uniform
+      nks = nks < 16 ? nks : 16;
+      const unsigned exa = lds0 + kFOffEx + (tq & 1) * 16384 + ex_tr;
+      const unsigned ka = lds0 + kFOffK + k_tr;
+      f32x16_t acc1;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc1[r] = 0.f;
+      auto kstep = [&](int ks, f32x16_t& a_) {
+        union { s16x4_t h2[2]; bf16x8_t v; } fa, fb;
+#pragma unroll
+        for (int rr = 0; rr < 2; ++rr) {
+          const unsigned a = (exa ^ (rr ? 32u : 0u)) + (unsigned)(ks * 1024 + rr * 512);
+          const unsigned kk = (ka ^ (rr ? 32u : 0u)) + (unsigned)(ks * 4096 + rr * 2048);
+          fa.h2[rr] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(reinterpret_cast<s16x4_t __attribute__((address_space(3)))*>(a));
+          fb.h2[rr] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(reinterpret_cast<s16x4_t __attribute__((address_space(3)))*>(kk));
+        }
+        a_ = mfma(fa.v, fb.v, a_);
+      };
+      __builtin_amdgcn_s_setprio(1);
+      int ks0 = 0;
+#pragma nounroll
+      for (; ks0 + 4 <= nks; ks0 += 4) {                 // four key steps at a time: their fragment reads go out ahead of the MFMAs
+        kstep(ks0, acc); kstep(ks0 + 1, acc1); kstep(ks0 + 2, acc); kstep(ks0 + 3, acc1);
+      }
+      if (ks0 < nks) { kstep(ks0, acc); kstep(ks0 + 1, acc1); }
+      __builtin_amdgcn_s_setprio(0);
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[r] += acc1[r];
+    };
+    // (c) the tile goes out
+    auto dq_put = [&](int tq, const f32x16_t& acc) {
+      int ln = lane;
+      asm volatile("" : "+v"(ln));
+      const int qrow0 = (jb + tq) * kFBQ;
+      // Everything older than the tile loads this iteration issued has to be complete BEFORE the stores below go out:
+      // loads and stores retire out of order with respect to each other, so once stores are in flight the counter no
+      // longer tells whether the next block's tile has landed (the next iteration does not wait for it again).
+      if (wave == 0) wait_vmcnt<3>(); else wait_vmcnt<2>();
+      auto put = [&](int r) {
+        if (DQ == kDqAtomic) __builtin_amdgcn_global_atomic_fadd_f32((__attribute__((address_space(1))) float*)dq_at(tq, ln, r), acc[r]);
+        else __hip_atomic_store(dq_at(tq, ln, r), acc[r], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      };
+      if (qrow0 + kFBQ <= S) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) put(r);
+      } else {
+        const int qlane = qrow0 + 4 * (ln >> 5);
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+          if (qlane + 8 * (r >> 2) + (r & 3) < S) put(r);
+      }
+    };
+
+    wait_vmcnt<0>();                                     // V rows in registers; the key tile and the first blocks too (once per key block)
+    for (int t = 0; t < nblk; ++t) {
+      // Block t has landed and block t - 1's dS is complete in its exchange tile after this barrier.  A wavefront that
+      // did phase 2 in the previous iteration has waited for all of its loads there (before its stores went out), so it
+      // must not wait here for those stores.
+      const bool had_turn = t > 1 && (wave >> 2) == ((t - 1) & 1);
+      if (!had_turn) {
+        if (t + 1 < nblk) { if (wave == 0) wait_vmcnt<3>(); else wait_vmcnt<2>(); }
+        else wait_vmcnt<0>();
+      }
+      stage_barrier();
+      if (t + 2 < nblk) issue(t + 2);
+      const bool turn = t > 0 && (wave >> 2) == (t & 1);  // this wavefront produces the dQ tile of block t - 1 in this iteration
+      f32x16_t dqacc;
+      if (turn) dq_fetch(t - 1, dqacc);
+      const int qb0 = (jb + t) * kFBQ;
+      if (qb0 + kFBQ - 1 >= kv0w) {                       // else no query of the block sees this wavefront's keys: its rows of Ex^T are not read
+        const unsigned so = lds0 + kFOffRing + (t % kFStages) * kFStage;
+        const unsigned nat_t = la.nat + so, tr_t = la.tr + so;
+        const unsigned sl = so + 16384 + 16 * hh;          // lse, then D, of the block's rows 4 hh ..
+        typedef const __attribute__((address_space(3))) f32x4_t* lds_f4_t;
+        bf16x8_t pb[2], dsb[2];
+        {
+          // S = Q K^T and dP = dO V^T: two independent accumulation chains, issued alternately
+          f32x16_t sacc, pacc;
+#pragma unroll
+          for (int r = 0; r < 16; ++r) { sacc[r] = 0.f; pacc[r] = 0.f; }
+          __builtin_amdgcn_s_setprio(1);
+          static_for<8>([&](auto ks_c) {
+            TAW_CONST(ks, ks_c);
+            sacc = mfma(frag_nat2<ks, 0, true>(nat_t), frag_nat2<ks, 0, true>(knat_t), sacc);
+            pacc = mfma(frag_nat2<ks, 8192, true>(nat_t), vf[ks], pacc);
+          });
+          __builtin_amdgcn_s_setprio(0);
+          if (qb0 < kv0w + 31) {                           // block crosses the diagonal (wavefront-uniform)
+            asm volatile("" ::: "memory");
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+              const int qi = qb0 + 8 * (r >> 2) + 4 * hh + (r & 3);
+              sacc[r] = kvi > qi ? -INFINITY : sacc[r];
+            }
+          }
+#pragma unroll
+          for (int r4 = 0; r4 < 4; ++r4) {
+            const f32x4_t l4 = *reinterpret_cast<lds_f4_t>(sl + (8 * r4) * 4);     // +inf for rows beyond S: p = 0
+            const f32x4_t d4 = *reinterpret_cast<lds_f4_t>(sl + (32 + 8 * r4) * 4);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              const int r = 4 * r4 + e;
+              const float pr = fast_exp2(__builtin_fmaf(sacc[r], c, -l4[e]));
+              sacc[r] = pr;
+              pacc[r] = pr * (pacc[r] - d4[e]);
+            }
+          }
+#pragma unroll
+          for (int tt = 0; tt < 2; ++tt) { pb[tt] = pack8(sacc, tt); dsb[tt] = pack8(pacc, tt); }
+        }
+        // dS -> exchange tile t & 1: rows = this wavefront's keys, four 8-byte pieces (4 consecutive query rows each) per lane
+        {
+          int ln = lane;
+          asm volatile("" : "+v"(ln));
+          const unsigned row = (unsigned)(32 * wave + (ln & 31));
+          const unsigned exw = lds0 + kFOffEx + (t & 1) * 16384 + row * 64u + 8u * (unsigned)(ln >> 5);
+          const unsigned sw = (row >> 2) & 3;
+#pragma unroll
+          for (int tt = 0; tt < 2; ++tt) {
+            const u32x4_t w = __builtin_bit_cast(u32x4_t, dsb[tt]);
+#pragma unroll
+            for (int half = 0; half < 2; ++half) {
+              const unsigned a = exw + (((unsigned)(2 * tt + half) ^ sw) << 4);
+              typedef unsigned int u32x2_t __attribute__((ext_vector_type(2)));
+              *reinterpret_cast<__attribute__((address_space(3))) u32x2_t*>(a) = u32x2_t{w[2 * half], w[2 * half + 1]};
+            }
+          }
+        }
+        __builtin_amdgcn_s_setprio(1);
+        static_for<4>([&](auto dt_c) {
+          TAW_CONST(dt, dt_c);
+          static_for<2>([&](auto tt_c) {
+            TAW_CONST(tt, tt_c);
+            bf16x8_t fq, fdo;
+            frag_tr2x2<tt, dt, 0, 8192, true>(tr_t, fq, fdo);
+            dv[dt] = mfma(fdo, pb[tt], dv[dt]);
+            dk[dt] = mfma(fq, dsb[tt], dk[dt]);
+          });
+        });
+        __builtin_amdgcn_s_setprio(0);
+      }
+      if (turn) {
+        dq_mfma(t - 1, dqacc);
+        dq_put(t - 1, dqacc);
+      }
+    }
+    wait_vmcnt<0>();
+    stage_barrier();                                     // the last block's dS is complete
+    if ((wave >> 2) == (nblk & 1)) {
+      f32x16_t dqacc;
+      dq_fetch(nblk - 1, dqacc);
+      dq_mfma(nblk - 1, dqacc);
+      dq_put(nblk - 1, dqacc);
+    }
+    __syncthreads();                                     // LDS becomes the output staging area
+
+    bf16_t* stage = reinterpret_cast<bf16_t*>(lds_raw) + wave * (32 * 136);
+    bf16_t* dkout = dqkv + (int64_t)b * S * ld + H + (int64_t)h * D;
+    bf16_t* dvout = dkout + H;
+    if (rope) {
+      int ln = lane;
+      asm volatile("" : "+v"(ln));
+      rope_inverse_T(dk, rope, kv0w + (ln & 31), S, ln);
+    }
+    store_rows_T(dk, scale, stage, dkout, ld, kv0w, S, lane);
+    store_rows_T(dv, 1.0f, stage, dvout, ld, kv0w, S, lane);
+  }
+}
+
+// dq = bf16( rotate_back( scale * sum of the slots that hold row t ) ): slot s holds the rows from 256 s on (the first key
+// block of its worker), so row t at position p reads slots 0 .. min(Ns - 1, p / 256).  One thread per 8 columns.
+__global__ void __launch_bounds__(256) attn_bwd_dq_reduce_kernel(const float* __restrict__ slots, int Ns, int64_t slot_stride,
+                                                                 bf16_t* __restrict__ dqkv, int64_t rows, int S, int H, float scale,
+                                                                 const float* __restrict__ rope) {
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  const int cpr = H / 8;
+  if (idx >= rows * cpr) return;
+  const int64_t row = idx / cpr;
+  const int col = (int)(idx % cpr) * 8;
+  const int pos = (int)(row % S);
+  int ns = pos / 256 + 1;
+  ns = ns < Ns ? ns : Ns;
+  float v[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  const float* p = slots + row * (int64_t)H + col;
+  for (int s = 0; s < ns; ++s) {
+    const f32x4_t a = __builtin_nontemporal_load(reinterpret_cast<const f32x4_t*>(p + s * slot_stride));
+    const f32x4_t b2 = __builtin_nontemporal_load(reinterpret_cast<const f32x4_t*>(p + s * slot_stride + 4));
+#pragma unroll
+    for (int e = 0; e < 4; ++e) { v[e] += a[e]; v[4 + e] += b2[e]; }
+  }
+  if (rope) {
+    const float* tb = rope + ((int64_t)pos * (D / 2) + (col % D) / 2) * 2;
+    const f32x4_t cs0 = *reinterpret_cast<const f32x4_t*>(tb), cs1 = *reinterpret_cast<const f32x4_t*>(tb + 4);
+    const float cc[4] = {cs0[0], cs0[2], cs1[0], cs1[2]}, sn[4] = {cs0[1], cs0[3], cs1[1], cs1[3]};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const float a = v[2 * e], b2 = v[2 * e + 1];
+      v[2 * e] = a * cc[e] + b2 * sn[e];
+      v[2 * e + 1] = b2 * cc[e] - a * sn[e];
+    }
+  }
+  bf16x8_t o;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) o[e] = (bf16_t)(v[e] * scale);
+  *reinterpret_cast<bf16x8_t*>(dqkv + row * (int64_t)(3 * H) + col) = o;
+}
+
+__global__ void __launch_bounds__(256) zero_f32_kernel(f32x4_t* __restrict__ p, size_t nvec) {
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < nvec; i += (size_t)gridDim.x * 256) p[i] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+}
+
 int launch_fwd(int B, int S, int nh, const void* qkv, void* o, float* lse, hipStream_t st) {
   constexpr int BQ = 256;
   constexpr size_t lds = 4 * 2 * kTileBytes;      // the ring; the output staging (8 x 32 x 136 bf16) fits inside
@@ -788,20 +1167,69 @@ int launch_attn_fwd_mfma(int B, int S, int nh, const void* qkv, void* o, float* 
   return launch_fwd(B, S, nh, qkv, o, lse, st);
 }
 
-size_t attn_bwd_mfma_scratch_floats(int B, int S, int nh) { return 2 * (size_t)B * nh * ((S + 63) / 64 * 64); }
+// Workers per (batch, head) for the slot form: as many as fill the 256 compute units in whole rounds, preferring few (every
+// slot is one more fp32 copy of dQ to write and to sum).  At most one worker per key block.
+int attn_bwd_slots(int B, int S, int nh) {
+  constexpr int kCUs = 256;
+  const int nkt = (S + 255) / 256;
+  int best = 1;
+  double best_score = -1.0;
+  for (int ns = 1; ns <= 16 && ns <= nkt; ++ns) {
+    const int64_t w = (int64_t)B * nh * ns;
+    const double eff = (double)w / (double)((w + kCUs - 1) / kCUs * kCUs);
+    const int rounds = (nkt + ns - 1) / ns;
+    const double balance = (rounds & 1) && rounds < 8 ? 1.0 - 0.5 / rounds : 1.0;     // an odd, small number of snake rounds leaves the workers uneven
+    const double score = eff * balance - 0.004 * ns;
+    if (score > best_score) { best_score = score; best = ns; }
+  }
+  return best;
+}
+
+size_t attn_bwd_mfma_scratch_floats(int B, int S, int nh, bool with_slots) {
+  const size_t prep = 2 * (size_t)B * nh * ((S + 63) / 64 * 64);
+  if (!with_slots) return prep;
+  return prep + (size_t)attn_bwd_slots(B, S, nh) * (size_t)B * S * nh * D;      // one slot suffices for the atomic form
+}
 
 int launch_attn_bwd_mfma(int B, int S, int nh, const void* qkv, const void* o, const void* dO, const float* lse, float* prep,
-                         void* dqkv, const float* rope_table, hipStream_t st) {
+                         void* dqkv, const float* rope_table, int form, hipStream_t st) {
   const float scale = 1.0f / sqrtf((float)D);
   const int Sp = (S + 63) / 64 * 64;
   const float* lse2 = prep;
   const float* Dv = prep + (size_t)B * nh * Sp;
+  float* slots = prep + 2 * (size_t)B * nh * Sp;
   {
     const int64_t threads = (int64_t)B * Sp * nh * 16;
     hipLaunchKernelGGL(attn_bwd_prep_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st, (const bf16_t*)o, (const bf16_t*)dO, lse, prep,
                        B, S, Sp, nh);
     int rc = (int)hipGetLastError();
     if (rc) return rc;
+  }
+  if (form == ATTN_BWD_FUSED || form == ATTN_BWD_FUSED_ATOMIC) {
+    const int64_t H = (int64_t)nh * D, rows = (int64_t)B * S;
+    const int nkt = (S + 255) / 256;
+    int ns = 1;
+    if (form == ATTN_BWD_FUSED) {
+      ns = attn_bwd_slots(B, S, nh);
+      const int nworkers = B * nh * ns;
+      TAW_SET_LDS_LIMIT_ONCE((attn_bwd_fused_kernel<kDqSlots>), kFusedLds);
+      hipLaunchKernelGGL((attn_bwd_fused_kernel<kDqSlots>), dim3((unsigned)nworkers), dim3(kThreads8), kFusedLds, st, (const bf16_t*)qkv,
+                         (const bf16_t*)dO, prep, (bf16_t*)dqkv, slots, B, S, Sp, nh, scale, rope_table, ns, nworkers);
+    } else {
+      const size_t nvec = (size_t)rows * H / 4;
+      hipLaunchKernelGGL(zero_f32_kernel, dim3(2048), dim3(256), 0, st, reinterpret_cast<f32x4_t*>(slots), nvec);
+      int rc = (int)hipGetLastError();
+      if (rc) return rc;
+      TAW_SET_LDS_LIMIT_ONCE((attn_bwd_fused_kernel<kDqAtomic>), kFusedLds);
+      hipLaunchKernelGGL((attn_bwd_fused_kernel<kDqAtomic>), dim3((unsigned)(nkt * B * nh)), dim3(kThreads8), kFusedLds, st, (const bf16_t*)qkv,
+                         (const bf16_t*)dO, prep, (bf16_t*)dqkv, slots, B, S, Sp, nh, scale, rope_table, 1, nkt * B * nh);
+    }
+    int rc = (int)hipGetLastError();
+    if (rc) return rc;
+    const int64_t n = rows * (H / 8);
+    hipLaunchKernelGGL(attn_bwd_dq_reduce_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, slots, ns, rows * H, (bf16_t*)dqkv, rows, S,
+                       (int)H, scale, rope_table);
+    return (int)hipGetLastError();
   }
   {
     constexpr size_t lds = 4 * (2 * kTileBytes + 2 * 64 * sizeof(float));

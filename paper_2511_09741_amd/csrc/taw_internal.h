@@ -85,11 +85,21 @@ int launch_gemm_mfma_nt_rope(int64_t M, int64_t N, int64_t K, const void* A, int
 // bf16, head_dim 128, and S * 3 * n_heads * head_dim * 2 bytes below 4 GiB (32-bit row offsets inside one batch element)
 bool attn_mfma_supported(int dtype, int S, int nh, int d);
 int launch_attn_fwd_mfma(int B, int S, int nh, const void* qkv, void* o, float* lse, hipStream_t st);
-// fp32 scratch of the MFMA backward: scaled lse and D, each padded to a multiple of 64 rows per (batch, head)
-size_t attn_bwd_mfma_scratch_floats(int B, int S, int nh);
+// The MFMA backward exists in three forms.  SPLIT (default): a dK/dV kernel and a dQ kernel that each recompute S and dP
+// (7 matrix products per tile pair), no atomics, reproducible.  FUSED: one key-stationary kernel forms S and dP once
+// and produces dK, dV and dQ (5 products); dQ partial sums go to private fp32 slots, one per worker, and a last pass
+// sums them: no atomics, reproducible.  FUSED_ATOMIC: the fused kernel adding dQ with fp32 atomics into one buffer.
+// On this part the split pair is the fastest (S = 32768, 32 heads: 26.7 ms against 30.4 and 27.2): the atomic units
+// take 25.4 ms for the adds alone, and the slots move 69 GB through HBM that the recomputation does not.
+enum { ATTN_BWD_SPLIT = 0, ATTN_BWD_FUSED = 1, ATTN_BWD_FUSED_ATOMIC = 2 };
+// workers (and fp32 dQ slots) per (batch, head) the fused form uses for this shape
+int attn_bwd_slots(int B, int S, int nh);
+// fp32 scratch of the MFMA backward: scaled lse and D, each padded to a multiple of 64 rows per (batch, head); with_slots:
+// followed by the dQ slots of the fused forms
+size_t attn_bwd_mfma_scratch_floats(int B, int S, int nh, bool with_slots);
 // computes its own row statistics (scratch) from o, dO and lse.  rope_table != nullptr: q and k were rotated
 // (table [S, 64, 2] fp32 of cos, sin) and dq, dk come out as gradients of the unrotated q, k
 int launch_attn_bwd_mfma(int B, int S, int nh, const void* qkv, const void* o, const void* dO, const float* lse,
-                         float* scratch, void* dqkv, const float* rope_table, hipStream_t st);
+                         float* scratch, void* dqkv, const float* rope_table, int form, hipStream_t st);
 
 }  // namespace taw

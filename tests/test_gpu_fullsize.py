@@ -193,11 +193,12 @@ def test_backward_linears_paired_launch_sampled_blocks(taw, width):
         del dyy, W, x, G, G0, dx
 
 
-@pytest.mark.parametrize("width", WIDTHS)
-def test_attention_sampled(taw, width):
+@pytest.mark.parametrize("width,form", [(w, 2) for w in WIDTHS] + [("C3", 3), ("C4", 3)], ids=[w + "-split" for w in WIDTHS] + ["C3-fused", "C4-fused"])
+def test_attention_sampled(taw, width, form):
     """Attention at the layer's shape (all heads, all batch elements in one launch): o and lse at
     sampled (batch, head, row); dq, dk, dv on the last 300 positions, once as gradients of the q, k
-    passed in and once through the rotary backward (rope_table given)."""
+    passed in and once through the rotary backward (rope_table given).  The split backward (form 2, what
+    taw_layer_bwd runs) at every width, the fused form with dQ slots (form 3) at two (16 and 4 key blocks per worker)."""
     import torch
     cfg = I.CONFIGS[width]
     B, S, nh, d = cfg.B, cfg.S, cfg.n_heads, cfg.head_dim
@@ -212,8 +213,8 @@ def test_attention_sampled(taw, width):
     scratch = torch.empty(taw.taw_op_attn_bwd_scratch_floats(B, S, nh), dtype=torch.float32, device="cuda")
     table = torch.empty(S * (d // 2) * 2, dtype=torch.float32, device="cuda")
     taw.taw_rope_table_init(taw.desc_from_config(cfg, 0), table)
-    taw.taw_op_attn_bwd(BF, B, S, nh, d, qkv, o, dO, lse, dqkv, scratch, None, taw.TAW_IMPL_MFMA)
-    taw.taw_op_attn_bwd(BF, B, S, nh, d, qkv, o, dO, lse, dqkv_rot, scratch, table, taw.TAW_IMPL_MFMA)
+    taw.taw_op_attn_bwd(BF, B, S, nh, d, qkv, o, dO, lse, dqkv, scratch, None, form)
+    taw.taw_op_attn_bwd(BF, B, S, nh, d, qkv, o, dO, lse, dqkv_rot, scratch, table, form)
     torch.cuda.synchronize()
     rows = np.array([0, 1, 63, 64, 255, 256, 257, 8191, 8192, S // 2 + 3617, S - 1 - 256, S - 1])
     t0 = S - 300

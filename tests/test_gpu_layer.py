@@ -100,6 +100,30 @@ def test_bf16_layer_on_mfma_kernels(taw, B, S, nh, I_, sigma):
     U.check_layer(taw, cfg, seed=B + S, gamma_jitter=0.1)
 
 
+def test_bf16_layer_with_the_fused_attention_backward(taw):
+    """TAW_ATTN_BWD_FUSED: the layer's backward with the one-kernel attention backward (dQ partial sums in private
+    slots inside the workspace) against the oracle, and against the default pair of kernels (same tolerance; the two
+    differ in summation order only)."""
+    cfg = I.LayerConfig("bf16-fused-bwd", I.BF16, 2, 1100, 512, 4, 128, 1408, sigma_w=0.05)
+    w = I.make_weights(cfg, 7, gamma_jitter=0.1)
+    x, dy = I.make_activations(cfg, 7)
+    w64 = I.weights_to_f64(w, cfg.dtype)
+    from oracle import decoder_layer as O
+    yr, cache = O.layer_fwd(w64, I.to_f64(x, cfg.dtype), cfg.n_heads, cfg.rope_theta, cfg.rms_eps)
+    dxr, Gr = O.layer_bwd(w64, cache, I.to_f64(dy, cfg.dtype))
+    assert taw.taw_layer_workspace_bytes(taw.desc_from_config(cfg, taw.TAW_ATTN_BWD_FUSED)) > taw.taw_layer_workspace_bytes(taw.desc_from_config(cfg, 0))
+    for flags in (taw.TAW_ATTN_BWD_FUSED, 0):
+        L = U.DeviceLayer(taw, cfg, flags=flags)
+        L.set_weights(w)
+        xd, dyd = U.to_dev(x, cfg.dtype), U.to_dev(dy, cfg.dtype)
+        L.fwd(xd)
+        dx = L.bwd(xd, dyd)
+        assert U.tensor_scale_err(U.from_dev(dx), dxr) < U.TOL[cfg.dtype]
+        G = L.grads()
+        for k in Gr:
+            assert U.tensor_scale_err(G[k], Gr[k]) < U.TOL[cfg.dtype], (flags, k)
+
+
 def test_four_chained_layers_with_staged_weights(taw):
     """Config 4's pattern at reduced width (bf16, MFMA kernels): forward through layers 0..3, backward
     3..0, every layer's weights arriving through taw_weight_stage into one of two staging buffers on a

@@ -156,7 +156,7 @@ def test_swiglu_fwd_bwd(taw, dtype, T, I_):
     assert U.tensor_scale_err(U.from_dev(dgu), np.concatenate([dg, du], axis=1)) < tol
 
 
-def _attn_case(taw, dtype, B, S, nh, d, impl, seed=0, scale=1.0):
+def _attn_case(taw, dtype, B, S, nh, d, impl, seed=0, scale=1.0, bwd_impl=None):
     import torch
     rng = np.random.default_rng(seed)
     H = nh * d
@@ -184,7 +184,7 @@ def _attn_case(taw, dtype, B, S, nh, d, impl, seed=0, scale=1.0):
     lse_ref32 = torch.from_numpy(lref.astype(np.float32).reshape(-1)).cuda()
     dqkv = U.empty_dev((B * S, 3 * H), dtype)
     scratch = torch.empty(taw.taw_op_attn_bwd_scratch_floats(B, S, nh), dtype=torch.float32, device="cuda")
-    taw.taw_op_attn_bwd(dtype, B, S, nh, d, qkvd, U.to_dev(o_st, dtype), U.to_dev(dO, dtype), lse_ref32, dqkv, scratch, None, impl)
+    taw.taw_op_attn_bwd(dtype, B, S, nh, d, qkvd, U.to_dev(o_st, dtype), U.to_dev(dO, dtype), lse_ref32, dqkv, scratch, None, impl if bwd_impl is None else bwd_impl)
     got = U.from_dev(dqkv)
     # at S = 1 the exact dq and dk are identically zero: measure them on the scale of dv
     fl = 1e-3 * float(np.max(np.abs(dref[:, 2 * H:])))
@@ -280,15 +280,43 @@ def test_gemm_mfma_fp32_output_is_accurate(taw):
         assert err < 2e-6, (mode, err)
 
 
-@pytest.mark.parametrize("B,S,nh", [(1, 64, 1), (1, 256, 2), (2, 333, 2), (1, 1, 1), (1, 1000, 1), (1, 130, 3)])
-def test_attention_mfma(taw, B, S, nh):
-    """Tiled online-softmax kernels: several query/key tiles, ragged S, S = 1, more than one head and batch."""
-    _attn_case(taw, I.BF16, B, S, nh, 128, taw.TAW_IMPL_MFMA, seed=S + nh)
+# the three forms of the MFMA backward: the split dK/dV + dQ pair (the default), fused with private dQ slots, fused with atomics
+BWD_FORMS = {"split": 2, "fused": 3, "atomic": 4}
 
 
-def test_attention_mfma_peaked_scores(taw):
+@pytest.mark.parametrize("form", list(BWD_FORMS))
+@pytest.mark.parametrize("B,S,nh", [(1, 64, 1), (1, 256, 2), (2, 333, 2), (1, 1, 1), (1, 1000, 1), (1, 130, 3), (1, 2081, 2), (3, 520, 1), (4, 2304, 16)])
+def test_attention_mfma(taw, B, S, nh, form):
+    """Tiled online-softmax kernels: several query/key tiles, ragged S, S = 1, more than one head and batch; every
+    form of the backward (2081 keys: nine key blocks dealt to several workers per head in the fused form, each adding
+    into its slot more than once; 520: a last query block with rows beyond the sequence; 4 x 16 heads x 2304: four workers per head with up to three key blocks each)."""
+    _attn_case(taw, I.BF16, B, S, nh, 128, taw.TAW_IMPL_MFMA, seed=S + nh, bwd_impl=BWD_FORMS[form])
+
+
+@pytest.mark.parametrize("form", list(BWD_FORMS))
+def test_attention_mfma_peaked_scores(taw, form):
     """Scores of order 10: the running maximum moves a lot between key tiles."""
-    _attn_case(taw, I.BF16, 1, 700, 2, 128, taw.TAW_IMPL_MFMA, seed=9, scale=3.0)
+    _attn_case(taw, I.BF16, 1, 700, 2, 128, taw.TAW_IMPL_MFMA, seed=9, scale=3.0, bwd_impl=BWD_FORMS[form])
+
+
+def test_attention_backward_fused_form_is_reproducible(taw):
+    """The fused backward with slots adds its dQ partial sums in a fixed order (no atomics): two runs give the same bits."""
+    import torch
+    B, S, nh, d = 2, 1500, 3, 128
+    H = nh * d
+    qkv = I.device_normal((B * S, 3 * H), seed=5, std=0.7)
+    dO = I.device_normal((B * S, H), seed=6, std=1.0)
+    o = torch.empty((B * S, H), dtype=torch.bfloat16, device="cuda")
+    lse = torch.empty(B * nh * S, dtype=torch.float32, device="cuda")
+    taw.taw_op_attn_fwd(I.BF16, B, S, nh, d, qkv, o, lse, taw.TAW_IMPL_MFMA)
+    outs = []
+    for fill in (0.0, 1e30):
+        scratch = torch.full((taw.taw_op_attn_bwd_scratch_floats(B, S, nh),), fill, dtype=torch.float32, device="cuda")   # stale contents must not matter
+        dqkv = torch.empty_like(qkv)
+        taw.taw_op_attn_bwd(I.BF16, B, S, nh, d, qkv, o, dO, lse, dqkv, scratch, None, taw.TAW_IMPL_MFMA_FUSED)
+        torch.cuda.synchronize()
+        outs.append(dqkv)
+    assert torch.equal(outs[0], outs[1])
 
 
 @pytest.mark.parametrize("dtype", [I.F32, I.BF16])
