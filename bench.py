@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the decoder-layer hot path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload default|C2|C3|C4|C5|P-<H>-<S>|paper-sweep]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload default|C2|C3|C4|C5|P-<H>-<S>|paper-sweep|diag]
 
 One step = one pass of the whole hot path over one micro-batch of synthetic input:
   taw_weight_stage   the other layer's weight chunk is copied owner-store -> staging buffer on a
@@ -37,6 +37,10 @@ Prints ONE JSON line.  Besides the contract fields it carries
                 aggregation on the compute stream instead of its side stream, and the event timestamps
                 of the copies against the steps that consume them
   recompute     the same step in activation-checkpointing mode (TAW_RECOMPUTE): same model FLOPs
+  measured_ceiling  a loop of nothing but bf16 MFMAs on random operands, timed in the same run: what the matrix cores
+                sustain under the part's power limit; every TFLOP/s roofline carries its fraction of that too
+--workload diag prints the probes of include/taw_diag.h instead (MFMA loop alone, with LDS reads, with loads; LDS read
+rate; dQ-update rates with atomics, stores, load-add-store; the GEMM kernel on 64 / 256 / 1024 tiles).
 """
 from __future__ import annotations
 
@@ -537,6 +541,58 @@ def run_c5(env, cfg, steps, warmup):
                         "delta_frac": round(ms_stage / ms_nostage - 1.0, 4)}}
 
 
+# =============================================================================== what the part sustains
+def mfma_ceiling(env):
+    """A loop of nothing but bf16 MFMAs on random operands (and on zeros): the rate the matrix cores sustain under the
+    part's power limit, measured in this run.  Every roofline fraction is quoted against this as well as against the
+    published peak."""
+    taw = env.taw
+    r = taw.taw_diag_mfma_loop(taw.TAW_DIAG_MFMA_RANDOM, 20000)
+    z = taw.taw_diag_mfma_loop(taw.TAW_DIAG_MFMA_ZERO, 20000)
+    return {"mfma_loop_random_operands_TFLOPs": round(r["TFLOPs"], 1), "clock_GHz": round(r["clock_GHz"], 3),
+            "mfma_loop_zero_operands_TFLOPs": round(z["TFLOPs"], 1), "clock_GHz_zero_operands": round(z["clock_GHz"], 3),
+            "what": "256 workgroups x 4 wavefronts issuing v_mfma_f32_32x32x16_bf16 back to back from registers (taw_diag_mfma_loop)"}
+
+
+def run_diag(env):
+    """The probes of include/taw_diag.h and the GEMM kernel on a quarter of the chip against the whole chip."""
+    torch, taw = env.torch, env.taw
+    src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda")
+    src.view(torch.int32).random_(0, 1 << 30)
+    names = {taw.TAW_DIAG_MFMA_RANDOM: "mfma_only_random_operands", taw.TAW_DIAG_MFMA_ZERO: "mfma_only_zero_operands",
+             taw.TAW_DIAG_MFMA_LDS: "mfma_plus_lds_fragment_reads", taw.TAW_DIAG_MFMA_LDS_LOADS: "mfma_plus_lds_reads_plus_global_to_lds_loads"}
+    out = {"mfma_loop": {}, "lds_read_bytes_per_clock_per_cu": {}, "dq_update": {}, "gemm_by_tiles": []}
+    for kind, name in names.items():
+        r = taw.taw_diag_mfma_loop(kind, 20000, src)
+        out["mfma_loop"][name] = {k: round(v, 3) for k, v in r.items()}
+    for instr, iname in enumerate(("ds_read_b128", "ds_read_b64", "ds_read_b64_tr_b16")):
+        for waves in (4, 8):
+            r = taw.taw_diag_lds_read_rate(instr, waves)
+            out["lds_read_bytes_per_clock_per_cu"][f"{iname}, {waves} wavefronts"] = round(r["bytes_per_clock_per_cu"], 1)
+    del src
+    for S in (8192, 32768):
+        buf = torch.empty(S * 32 * 128, dtype=torch.float32, device="cuda")
+        for mode, mname in enumerate(("fp32 atomic add (no return)", "plain store", "load + add + store")):
+            r = taw.taw_diag_dq_update_rate(buf, S, 32, mode)
+            out["dq_update"][f"S={S}, 32 heads, {mname}"] = {"ms": round(r["ms"], 3), "G_updates_per_s": round(r["updates_per_s"] / 1e9, 1)}
+        del buf
+    # the product GEMM (NT, bf16, K = 4096) on 64, 256 and 1024 output tiles: the same kernel and the same work per tile; what changes
+    # is how many compute units draw power at once
+    BF = taw.TAW_BF16
+    for (M, N) in ((2048, 2048), (4096, 4096), (8192, 8192)):
+        K = 4096
+        A = torch.empty(M * K, dtype=torch.bfloat16, device="cuda").normal_()
+        Bm = torch.empty(N * K, dtype=torch.bfloat16, device="cuda").normal_()
+        Cm = torch.empty(M * N, dtype=torch.bfloat16, device="cuda")
+        t = env.ev_time(lambda: taw.taw_op_gemm(BF, taw.TAW_GEMM_NT, M, N, K, A, K, Bm, K, Cm, N, BF, 0, None, 0, taw.TAW_IMPL_MFMA, env.compute), 20)
+        tiles = (M // 256) * (N // 256)
+        tf = 2.0 * M * N * K / t / 1e9
+        out["gemm_by_tiles"].append({"M": M, "N": N, "K": K, "tiles": tiles, "ms": round(t, 4), "TFLOPs": round(tf, 1),
+                                     "TFLOPs_per_busy_compute_unit": round(tf / min(tiles, 256), 2)})
+        del A, Bm, Cm
+    return out
+
+
 # =============================================================================== CPU oracle beside it
 def cpu_baseline(env):
     """The fp64 numpy oracle, as it stands, on one whole C2 layer (forward + backward), all host cores numpy uses."""
@@ -577,6 +633,9 @@ def main():
     env = Env()
     I = env.I
     wl = args.workload
+    if wl == "diag":
+        print(json.dumps({"diag": run_diag(env)}))
+        return
     extra = {}
     kl, rl = not args.no_kernel_leg, not args.no_recompute_leg
     if wl == "default":
@@ -620,6 +679,11 @@ def main():
                                           "paper_tawpipe_tokens_per_s_per_gpu": PAPER_TABLE_TAWPIPE.get((cfg.H, cfg.S))}],
                                 "paper_setup": PAPER_SETUP}
 
+    ceiling = mfma_ceiling(env)
+    for obj in [top.get("roofline")] + list((top.get("rooflines") or {}).values()) + [extra.get("c2", {}).get("roofline")] + \
+            list((extra.get("c2", {}).get("rooflines") or {}).values()):
+        if obj and obj.get("unit") == "TFLOP/s":
+            obj["frac_of_measured_mfma_loop"] = round(obj["achieved"] / ceiling["mfma_loop_random_operands_TFLOPs"], 4)
     cpu = None if args.no_cpu_baseline else cpu_baseline(env)
 
     metric = "layer fwd+bwd TFLOP/s (model FLOPs; fraction of the bf16 MFMA peak in config)"
@@ -632,7 +696,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": top["workload"], "model_flops_per_step": top["model_flops_per_step"],
                    "frac_of_bf16_mfma_peak": top["frac_of_bf16_mfma_peak"]},
-        "roofline": top.get("roofline"), "cpu_baseline": cpu,
+        "roofline": top.get("roofline"), "cpu_baseline": cpu, "measured_ceiling": ceiling,
     }
     for k in ("rooflines", "kernels", "overlap", "recompute", "ms_per_layer", "ms_per_microbatch"):
         if k in top:

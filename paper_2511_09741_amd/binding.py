@@ -39,6 +39,10 @@ class taw_adamw_desc(C.Structure):
                 ("weight_decay", C.c_float), ("grad_scale", C.c_float), ("step", C.c_int32), ("zero_grad", C.c_int32)]
 
 
+class taw_diag_rate(C.Structure):
+    _fields_ = [("tflops", C.c_double), ("clock_ghz", C.c_double), ("mfma_busy", C.c_double), ("ms", C.c_double)]
+
+
 class taw_sched_desc(C.Structure):
     _fields_ = [("P", C.c_int32), ("D", C.c_int32), ("L", C.c_int32), ("N", C.c_int32)]
 
@@ -68,6 +72,9 @@ _SIGS = {
     "taw_sched_update_step": (C.c_int, [C.POINTER(taw_sched_desc), _i32, C.POINTER(_i32)]),
     "taw_sched_bubble_ratio": (C.c_int, [C.POINTER(taw_sched_desc), C.POINTER(C.c_double), C.POINTER(C.c_double)]),
     "taw_sched_comm_elems": (C.c_int, [_i32, _i32, _i32, _i32] + [C.POINTER(C.c_double)] * 3),
+    "taw_diag_mfma_loop": (C.c_int, [_i32, _i32, _vp, _sz, C.POINTER(taw_diag_rate)]),
+    "taw_diag_lds_read_rate": (C.c_int, [_i32, _i32, C.POINTER(C.c_double), C.POINTER(C.c_double)]),
+    "taw_diag_dq_update_rate": (C.c_int, [_vp, _i32, _i32, _i32, C.POINTER(C.c_double), C.POINTER(C.c_double)]),
     "taw_status_string": (C.c_char_p, [C.c_int]),
     "taw_last_error": (C.c_char_p, []),
     "taw_op_gemm": (C.c_int, [_i32, _i32, _i64, _i64, _i64, _vp, _i64, _vp, _i64, _vp, _i64, _i32, _i32, _vp, _i64, _i32, _vp]),
@@ -289,3 +296,26 @@ def taw_op_qkv_rope(dtype, B, S, n_heads, head_dim, xn, w_qkv, qkv, rope_table, 
 
 def taw_op_linear_bwd(dtype, T, N, K, dy, W, x, dx, G, accumulate=0, impl=TAW_IMPL_AUTO, stream=None):
     _check(load().taw_op_linear_bwd(dtype, T, N, K, _p(dy), _p(W), _p(x), _p(dx), _p(G), accumulate, impl, _stream(stream)))
+
+
+# ----------------------------------------------------------------------------- taw_diag.h (each call waits for its kernel)
+TAW_DIAG_MFMA_RANDOM, TAW_DIAG_MFMA_ZERO, TAW_DIAG_MFMA_LDS, TAW_DIAG_MFMA_LDS_LOADS = 0, 1, 2, 3
+
+
+def taw_diag_mfma_loop(kind, iters=20000, src=None) -> dict:
+    out = taw_diag_rate()
+    nbytes = 0 if src is None else src.numel() * src.element_size()
+    _check(load().taw_diag_mfma_loop(kind, iters, _p(src), nbytes, C.byref(out)))
+    return {"TFLOPs": out.tflops, "clock_GHz": out.clock_ghz, "mfma_busy": out.mfma_busy, "ms": out.ms}
+
+
+def taw_diag_lds_read_rate(instr, waves) -> dict:
+    a, b = C.c_double(), C.c_double()
+    _check(load().taw_diag_lds_read_rate(instr, waves, C.byref(a), C.byref(b)))
+    return {"bytes_per_clock_per_cu": a.value, "clock_GHz": b.value}
+
+
+def taw_diag_dq_update_rate(buf, S, n_heads, mode) -> dict:
+    a, b = C.c_double(), C.c_double()
+    _check(load().taw_diag_dq_update_rate(_p(buf), S, n_heads, mode, C.byref(a), C.byref(b)))
+    return {"updates_per_s": a.value, "ms": b.value}

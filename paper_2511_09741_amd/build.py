@@ -15,7 +15,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libtaw.so")
-SOURCES = ["taw_api.hip", "taw_sched.hip", "kernels_bw.hip", "kernels_generic.hip", "gemm_mfma.hip", "attn_mfma.hip"]
+SOURCES = ["taw_api.hip", "taw_sched.hip", "kernels_bw.hip", "kernels_generic.hip", "gemm_mfma.hip", "attn_mfma.hip", "diag.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

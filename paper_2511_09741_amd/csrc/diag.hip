@@ -52,16 +52,21 @@ __global__ void __launch_bounds__(256, 1) mfma_loop_kernel(int iters, const unsi
   // loads of kind 3 land in the second half of LDS (this wavefront's 16 KiB), a different KiB per load of a step
   const unsigned dma_dst = lds0 + 65536 + wave * 16384;
   unsigned goff = (unsigned)((blockIdx.x * 4 + wave) * 65536u + lane * 16u);
+  u32x4_t pend[2];
+  if (KIND >= TAW_DIAG_MFMA_LDS) {
+    asm volatile("ds_read_b128 %0, %1" : "=v"(pend[0]) : "v"(rd));
+    asm volatile("ds_read_b128 %0, %1" : "=v"(pend[1]) : "v"(rd + 1024));
+  }
   const long long w0 = wall_clock64(), c0 = clock64();
   for (int it = 0; it < iters; ++it) {
 #pragma unroll
     for (int u = 0; u < 16; ++u) {
-      if (KIND >= TAW_DIAG_MFMA_LDS && (u & 1) == 0) {             // one fragment read per two MFMAs
-        u32x4_t v;
-        asm volatile("ds_read_b128 %0, %1" : "=v"(v) : "v"(rd + ((u >> 1) & 7) * 1024 + ((it & 1) ? 8192 : 0)));
-        asm volatile("s_waitcnt lgkmcnt(1)" ::: "memory");
-        if ((u >> 1) & 1) fa[(u >> 2) & 1].v = __builtin_bit_cast(bf16x8_t, v);
-        else fb[(u >> 2) & 1].v = __builtin_bit_cast(bf16x8_t, v);
+      if (KIND >= TAW_DIAG_MFMA_LDS && (u & 1) == 0) {             // one fragment read per two MFMAs, consumed four MFMAs after it was issued
+        const int slot = (u >> 1) & 1;
+        asm volatile("s_waitcnt lgkmcnt(1)" ::: "memory");         // all but the newest read have returned: pend[slot] is the older of the two
+        if ((u >> 1) & 2) fa[slot].v = __builtin_bit_cast(bf16x8_t, pend[slot]);
+        else fb[slot].v = __builtin_bit_cast(bf16x8_t, pend[slot]);
+        asm volatile("ds_read_b128 %0, %1" : "=v"(pend[slot]) : "v"(rd + ((u >> 1) & 7) * 1024 + ((it & 1) ? 8192 : 0)));
       }
       if (KIND == TAW_DIAG_MFMA_LDS_LOADS && (u & 3) == 0) {       // one direct load per four MFMAs
         asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(goff & src_mask), "s"((unsigned long long)src), "s"(dma_dst + (u >> 2) * 1024));

@@ -89,9 +89,9 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(REG ? 
     for (int i = 0; i < MAXC; ++i) {
       const int ci = i * 64 + lane;
       if (ci < nch) {
-        zc[i].load(z + base + ci * V);
-        dc[i].load(dout + base + ci * V);
-        if (dres) rs[i].load(dres + base + ci * V);
+        zc[i].load_nt(z + base + ci * V);              // each operand is streamed through once
+        dc[i].load_nt(dout + base + ci * V);
+        if (dres) rs[i].load_nt(dres + base + ci * V);
       }
     }
     const float rr = r[row];
@@ -131,7 +131,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(REG ? 
           if (dres) v += rs[i].get(j);
           o.set(j, v);
         }
-        o.store(dz + base + ci * V);
+        o.store_nt(dz + base + ci * V);
       }
     }
   }

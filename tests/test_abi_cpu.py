@@ -31,7 +31,7 @@ def declared_functions():
 
 def test_every_declared_symbol_is_exported(lib):
     names = declared_functions()
-    assert len(names) == 29
+    assert len(names) == 32
     for n in names:
         assert hasattr(lib, n), f"{n} declared in include/ but not exported"
     assert set(names) == set(taw.EXPORTS)
@@ -204,6 +204,21 @@ def test_op_validation(lib):
     with pytest.raises(taw.TawError) as e:
         taw.taw_op_attn_bwd(taw.TAW_BF16, 1, 16, 2, 128, ok, ok, ok, ok, ok, ok, ok + 4)
     assert e.value.status == taw.TAW_ERR_ALIGN           # rope_table given but misaligned
+
+
+def test_diag_validation(lib):
+    with pytest.raises(taw.TawError) as e:
+        taw.taw_diag_mfma_loop(7)
+    assert e.value.status == taw.TAW_ERR_SHAPE
+    with pytest.raises(taw.TawError) as e:
+        taw.taw_diag_mfma_loop(taw.TAW_DIAG_MFMA_LDS_LOADS)          # needs a source buffer
+    assert e.value.status == taw.TAW_ERR_NULL
+    with pytest.raises(taw.TawError) as e:
+        taw.taw_diag_lds_read_rate(0, 5)
+    assert e.value.status == taw.TAW_ERR_SHAPE
+    with pytest.raises(taw.TawError) as e:
+        taw.taw_diag_dq_update_rate(0x10000, 1000, 32, 0)            # S must be a multiple of 256
+    assert e.value.status == taw.TAW_ERR_SHAPE
 
 
 def test_missing_library_fails_loudly(monkeypatch, tmp_path):
