@@ -267,19 +267,26 @@ attn_fwd_kernel(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ o, float* _
   bf16x8_t pf[2][2];
   bool pend = false;
   unsigned pend_tr = 0;
+  // O^T += V^T P^T: 16 MFMAs, fragment i = (kb, t, dt) = (i / 8, (i / 4) % 2, i % 4).  The fragment reads run kAhead MFMAs
+  // ahead of their use, in registers of their own: an LDS read takes several MFMA issue slots to return, and a read placed
+  // right in front of its MFMA leaves the matrix pipe idle for that long, sixteen times per tile.  The scheduling barriers
+  // keep the compiler from moving the reads back next to their use.
+  constexpr int kAhead = 4;
   auto pv = [&](unsigned tr_t) {
+    bf16x8_t vfr[16];
+    auto rd = [&](auto i_c) {
+      TAW_CONST(i, i_c);
+      bf16x8_t unused;
+      frag_tr2x2<(i / 4) % 2, i % 4, kTileBytes + (i / 8) * 8192, -1>(tr_t, vfr[i], unused);
+    };
+    static_for<kAhead>(rd);
     __builtin_amdgcn_s_setprio(1);
-    static_for<2>([&](auto kb_c) {
-      TAW_CONST(kb, kb_c);
-      static_for<2>([&](auto t_c) {
-        TAW_CONST(t, t_c);
-        static_for<4>([&](auto dt_c) {
-          TAW_CONST(dt, dt_c);
-          bf16x8_t vfr, unused;
-          frag_tr2x2<t, dt, kTileBytes + kb * 8192, -1>(tr_t, vfr, unused);
-          oacc[dt] = mfma(vfr, pf[kb][t], oacc[dt]);
-        });
-      });
+    static_for<16>([&](auto i_c) {
+      TAW_CONST(i, i_c);
+      if constexpr (i + kAhead < 16) rd(std::integral_constant<int, i + kAhead>{});
+      __builtin_amdgcn_sched_barrier(0);
+      oacc[i % 4] = mfma(vfr[i], pf[i / 8][(i / 4) % 2], oacc[i % 4]);
+      __builtin_amdgcn_sched_barrier(0);
     });
     __builtin_amdgcn_s_setprio(0);
   };
@@ -302,18 +309,28 @@ attn_fwd_kernel(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ o, float* _
     const unsigned so = lds0 + (j & (NS - 1)) * kStage;
     const unsigned nat_t = la.nat + so, tr_t = la.tr + so;
 
+    // S^T = K Q^T: 16 MFMAs in two independent accumulation chains (the two 32-key halves of the tile), issued alternately;
+    // fragment reads kAhead MFMAs ahead, as in pv
     f32x16_t s[2];
-    __builtin_amdgcn_s_setprio(1);
-    static_for<2>([&](auto kb_c) {
-      TAW_CONST(kb, kb_c);
+    {
 #pragma unroll
-      for (int r = 0; r < 16; ++r) s[kb][r] = 0.f;
-      static_for<8>([&](auto ks_c) {
-        TAW_CONST(ks, ks_c);
-        s[kb] = mfma(frag_nat2<ks, kb * 8192>(nat_t), qf[ks], s[kb]);
+      for (int r = 0; r < 16; ++r) { s[0][r] = 0.f; s[1][r] = 0.f; }
+      bf16x8_t kfr[16];
+      auto rd = [&](auto i_c) {
+        TAW_CONST(i, i_c);
+        kfr[i] = frag_nat2<i / 2, (i % 2) * 8192>(nat_t);
+      };
+      static_for<kAhead>(rd);
+      __builtin_amdgcn_s_setprio(1);
+      static_for<16>([&](auto i_c) {
+        TAW_CONST(i, i_c);
+        if constexpr (i + kAhead < 16) rd(std::integral_constant<int, i + kAhead>{});
+        __builtin_amdgcn_sched_barrier(0);
+        s[i % 2] = mfma(kfr[i], qf[i / 2], s[i % 2]);
+        __builtin_amdgcn_sched_barrier(0);
       });
-    });
-    __builtin_amdgcn_s_setprio(0);
+      __builtin_amdgcn_s_setprio(0);
+    }
     if (kv0 + BKV - 1 > q0w) {                         // tile crosses the diagonal (or the end of the sequence)
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb)
@@ -721,13 +738,28 @@ attn_bwd_dq_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dO
       f32x16_t sacc, pacc;
 #pragma unroll
       for (int r = 0; r < 16; ++r) { sacc[r] = 0.f; pacc[r] = 0.f; }
-      __builtin_amdgcn_s_setprio(1);
-      static_for<8>([&](auto ks_c) {
-        TAW_CONST(ks, ks_c);
-        sacc = mfma(frag_nat2<ks, kb * 8192>(nat_t), qf[ks], sacc);
-        pacc = mfma(frag_nat2<ks, kTileBytes + kb * 8192>(nat_t), dof[ks], pacc);
-      });
-      __builtin_amdgcn_s_setprio(0);
+      {
+        // 16 MFMAs, the S^T and dP^T chains alternating; fragment i = (K or V, ks) = (i % 2, i / 2), read kAheadDq MFMAs ahead
+        // of its use into registers of its own (a read placed right in front of its MFMA idles the matrix pipe for the
+        // read's latency); the scheduling barriers keep the compiler from moving the reads back
+        constexpr int kAheadDq = 4;
+        bf16x8_t fr[16];
+        auto rd = [&](auto i_c) {
+          TAW_CONST(i, i_c);
+          fr[i] = frag_nat2<i / 2, (i % 2) * kTileBytes + kb * 8192>(nat_t);
+        };
+        static_for<kAheadDq>(rd);
+        __builtin_amdgcn_s_setprio(1);
+        static_for<16>([&](auto i_c) {
+          TAW_CONST(i, i_c);
+          if constexpr (i + kAheadDq < 16) rd(std::integral_constant<int, i + kAheadDq>{});
+          __builtin_amdgcn_sched_barrier(0);
+          if constexpr (i % 2 == 0) sacc = mfma(fr[i], qf[i / 2], sacc);
+          else pacc = mfma(fr[i], dof[i / 2], pacc);
+          __builtin_amdgcn_sched_barrier(0);
+        });
+        __builtin_amdgcn_s_setprio(0);
+      }
       if (need_mask) {                                   // wavefront-uniform
         asm volatile("" ::: "memory");                   // keeps this a branch: most tiles skip the compares
 #pragma unroll
@@ -741,18 +773,27 @@ attn_bwd_dq_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dO
         const float p = fast_exp2(__builtin_fmaf(sacc[r], c, -l2));
         pacc[r] = p * (pacc[r] - dsum);
       }
-      __builtin_amdgcn_s_setprio(1);
-      static_for<2>([&](auto t_c) {
-        TAW_CONST(t, t_c);
-        const bf16x8_t dsb = pack8(pacc, t);
-        static_for<4>([&](auto dt_c) {
-          TAW_CONST(dt, dt_c);
-          bf16x8_t fk, unused;
-          frag_tr2x2<t, dt, kb * 8192, -1>(tr_t, fk, unused);
-          dq[dt] = mfma(fk, dsb, dq[dt]);
+      {
+        // dQ^T += K^T dS^T: 8 MFMAs, fragment i = (t, dt) = (i / 4, i % 4), read ahead in the same way
+        constexpr int kAheadDq2 = 3;
+        const bf16x8_t dsb[2] = {pack8(pacc, 0), pack8(pacc, 1)};
+        bf16x8_t fk[8];
+        auto rd = [&](auto i_c) {
+          TAW_CONST(i, i_c);
+          bf16x8_t unused;
+          frag_tr2x2<i / 4, i % 4, kb * 8192, -1>(tr_t, fk[i], unused);
+        };
+        static_for<kAheadDq2>(rd);
+        __builtin_amdgcn_s_setprio(1);
+        static_for<8>([&](auto i_c) {
+          TAW_CONST(i, i_c);
+          if constexpr (i + kAheadDq2 < 8) rd(std::integral_constant<int, i + kAheadDq2>{});
+          __builtin_amdgcn_sched_barrier(0);
+          dq[i % 4] = mfma(fk[i], dsb[i / 4], dq[i % 4]);
+          __builtin_amdgcn_sched_barrier(0);
         });
-      });
-      __builtin_amdgcn_s_setprio(0);
+        __builtin_amdgcn_s_setprio(0);
+      }
     });
   }
   __syncthreads();          // the ring becomes the output staging area
