@@ -499,18 +499,24 @@ __global__ void __launch_bounds__(256) attn_bwd_prep_kernel(const bf16_t* __rest
 }
 
 // =============================================================================== backward: dK, dV
-// Workgroup: 8 wavefronts, one (batch, head, 256 keys); wavefront w owns keys 32w..32w+31 and keeps
-// their K and V rows in registers as B operands.  Query rows stream through a 4-stage LDS ring in
-// blocks of 64 (Q and dO tiles plus the rows' lse and D), from the diagonal to the end of the
-// sequence, filled by direct global->LDS loads three blocks ahead.
-//   S = Q K^T;  P = exp(S/sqrt(d) - lse);  dP = dO V^T;  dS = P (dP - D)
+// Workgroup: 8 wavefronts, one (batch, head, 256 keys); wavefront w owns keys 32w..32w+31.  Their V rows stay in
+// registers as B operands; their K rows are read from a copy of the key tile in LDS (64 KiB), which leaves the
+// registers for both score accumulators at once and for reading fragments ahead of the MFMAs.  Query rows stream
+// through a 2-stage LDS ring in blocks of 64 (Q and dO tiles plus the rows' lse and D), from the diagonal to the end
+// of the sequence, filled by direct global->LDS loads one block ahead (a block takes several microseconds to process,
+// more than a load takes to land).
+//   S = Q K^T and dP = dO V^T as two alternating accumulation chains;  P = exp(S/sqrt(d) - lse);  dS = P (dP - D)
 //   dV^T += dO^T P;   dK^T += Q^T dS  (scaled by 1/sqrt(d) at the end)
+constexpr int kKvOffRing = 65536;                                        // key tile [256][128] bf16 in front of the ring
+constexpr int kKvStage = 2 * kTileBytes + 2 * 64 * 4;                    // Q tile | dO tile | lse[64] | D[64]
+constexpr size_t kKvLds = kKvOffRing + 2 * kKvStage;
 __global__ void __launch_bounds__(kThreads8, 1)
 attn_bwd_dkv_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dO, const float* __restrict__ lse2,
                     const float* __restrict__ Dsum, bf16_t* __restrict__ dqkv, int B, int S, int Sp, int nh, float scale,
                     const float* __restrict__ rope) {
-  constexpr int BKVW = 256, BQ = 64, NS = 4;
-  constexpr int kStage = 2 * kTileBytes + 2 * BQ * 4;   // Q tile | dO tile | lse[64] | D[64]
+  constexpr int BKVW = 256, BQ = 64, NS = 2;
+  constexpr int kStage = kKvStage;
+  constexpr int kA = 1;                                // fragment reads run this many MFMA steps ahead of their use (deeper costs registers this kernel does not have)
   extern __shared__ __attribute__((aligned(256))) unsigned char lds_raw[];
   const lds_u8_t* L = (const lds_u8_t*)lds_raw;
   const unsigned lds0 = (unsigned)(size_t)L;
@@ -520,39 +526,46 @@ attn_bwd_dkv_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ d
   LaneAddr la;
   la.init(lane);
   const int bh = blockIdx.x % (B * nh);
-  const int kt = blockIdx.x / (B * nh);                 // early key tiles see the most queries: they go first
+  const int kt = blockIdx.x / (B * nh);
   const int b = bh / nh, h = bh % nh;
   const int64_t H = (int64_t)nh * D, ld = 3 * H;
   const bf16_t* qbase = qkv + (int64_t)b * S * ld + (int64_t)h * D;
   const bf16_t* kbase = qbase + H;
   const bf16_t* vbase = qbase + 2 * H;
-  const uint64_t qb64 = (uint64_t)qbase, do64 = (uint64_t)(dO + (int64_t)b * S * H + (int64_t)h * D);
+  const uint64_t qb64 = (uint64_t)qbase, k64 = (uint64_t)kbase, do64 = (uint64_t)(dO + (int64_t)b * S * H + (int64_t)h * D);
   const uint64_t l64 = (uint64_t)(lse2 + ((int64_t)b * nh + h) * Sp), d64 = (uint64_t)(Dsum + ((int64_t)b * nh + h) * Sp);
   const unsigned ldb = (unsigned)(ld * 2), ldob = (unsigned)(H * 2);
   const int kv0 = kt * BKVW, kv0w = kv0 + wave * 32;
   const float c = scale * kLog2e;
 
-  const int jb = kv0 / BQ, je = (S + BQ - 1) / BQ;      // query blocks jb .. je-1
+  const int jb = kv0 / BQ, je = (S + BQ - 1) / BQ;
   const int nblk = je - jb;
+  // key tile -> LDS (8 pieces of 4 rows per wavefront)
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const int j = wave + 8 * i;
+    const int r = 4 * j + (lane >> 4);
+    const int cc = swz(r, lane & 15);
+    int rg = kv0 + r;
+    rg = rg < S ? rg : S - 1;
+    lds_dma16(k64, (unsigned)rg * ldb + cc * 16, lds0 + j * 1024);
+  }
   auto issue = [&](int t) {
-    const unsigned st = lds0 + (t & (NS - 1)) * kStage;
+    const unsigned st = lds0 + kKvOffRing + (t & (NS - 1)) * kStage;
     const int row0 = (jb + t) * BQ;
     tile_dma(qb64, ldb, row0, S, st, lane, wave);
     tile_dma(do64, ldob, row0, S, st + kTileBytes, lane, wave);
-    if (wave < 2)                                       // wavefront 0: the block's scaled lse; wavefront 1: its D (both padded to Sp rows)
+    if (wave < 2)
       lds_dma4(wave == 0 ? l64 : d64, (unsigned)(row0 + lane) * 4u, st + 2 * kTileBytes + wave * (BQ * 4));
   };
-  for (int t = 0; t < NS - 1 && t < nblk; ++t) issue(t);
+  issue(0);
 
-  bf16x8_t kf[8], vf[8];
+  bf16x8_t vf[8];
   {
     int row = kv0w + (lane & 31);
     if (row >= S) row = S - 1;
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks) {
-      kf[ks] = *reinterpret_cast<const bf16x8_t*>(kbase + (int64_t)row * ld + 16 * ks + 8 * hh);
-      vf[ks] = *reinterpret_cast<const bf16x8_t*>(vbase + (int64_t)row * ld + 16 * ks + 8 * hh);
-    }
+    for (int ks = 0; ks < 8; ++ks) vf[ks] = *reinterpret_cast<const bf16x8_t*>(vbase + (int64_t)row * ld + 16 * ks + 8 * hh);
   }
   f32x16_t dk[4], dv[4];
 #pragma unroll
@@ -560,41 +573,48 @@ attn_bwd_dkv_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ d
 #pragma unroll
     for (int r = 0; r < 16; ++r) { dk[dt][r] = 0.f; dv[dt][r] = 0.f; }
   const int kvi = kv0w + (lane & 31);
+  const unsigned knat_t = la.nat + lds0 + wave * 8192;
 
-  // The register-resident operands loaded above have arrived: said here, once, so that the compiler
-  // does not wait for them (and with them for every tile load in flight) at their first use inside the loop.
-  wait_vmcnt<0>();
   for (int t = 0; t < nblk; ++t) {
-    const int ahead = nblk - 1 - t;
-    if (wave < 2) { if (ahead >= 2) wait_vmcnt<10>(); else if (ahead == 1) wait_vmcnt<5>(); else wait_vmcnt<0>(); }
-    else { if (ahead >= 2) wait_vmcnt<8>(); else if (ahead == 1) wait_vmcnt<4>(); else wait_vmcnt<0>(); }
+    wait_vmcnt<0>();                                     // block t (issued one iteration ago) has landed
     stage_barrier();
-    if (t + NS - 1 < nblk) issue(t + NS - 1);
+    if (t + 1 < nblk) issue(t + 1);                      // into the stage every wavefront finished reading before this barrier
     const int qb0 = (jb + t) * BQ;
-    if (qb0 + BQ - 1 < kv0w) continue;                   // no query of the block sees this wavefront's keys
-    const unsigned so = lds0 + (t & (NS - 1)) * kStage;
+    if (qb0 + BQ - 1 < kv0w) continue;
+    const unsigned so = lds0 + kKvOffRing + (t & (NS - 1)) * kStage;
     const unsigned nat_t = la.nat + so, tr_t = la.tr + so;
-    const unsigned sl = so + 2 * kTileBytes + 16 * hh;     // lse, then D, of the block's rows 4 hh ..
+    const unsigned sl = so + 2 * kTileBytes + 16 * hh;
     static_for<2>([&](auto qb_c) {
       TAW_CONST(qb, qb_c);
       const int qrow0 = qb0 + qb * 32;
-      if (qrow0 + 31 < kv0w) return;                     // wavefront-uniform
+      if (qrow0 + 31 < kv0w) return;
       typedef const __attribute__((address_space(3))) f32x4_t* lds_f4_t;
-      // S and P first; P is kept only as the bf16 operand of the dV product (dS below is formed from
-      // those rounded values too), so that the second accumulator does not have to coexist with the first
       bf16x8_t pb[2], dsb[2];
       {
-        f32x16_t sacc;
+        f32x16_t sacc, pacc;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) sacc[r] = 0.f;
+        for (int r = 0; r < 16; ++r) { sacc[r] = 0.f; pacc[r] = 0.f; }
+        // step i: S MFMA needs Q(i) and K(i) from LDS, dP MFMA needs dO(i)
+        bf16x8_t fq[8], fk[8], fo[8];
+        auto rd = [&](auto i_c) {
+          TAW_CONST(i, i_c);
+          fq[i] = frag_nat2<i, qb * 8192, true>(nat_t);
+          fk[i] = frag_nat2<i, 0, true>(knat_t);
+          fo[i] = frag_nat2<i, kTileBytes + qb * 8192, true>(nat_t);
+        };
+        static_for<kA>(rd);
         __builtin_amdgcn_s_setprio(1);
-        static_for<8>([&](auto ks_c) {
-          TAW_CONST(ks, ks_c);
-          sacc = mfma(frag_nat2<ks, qb * 8192, true>(nat_t), kf[ks], sacc);
+        static_for<8>([&](auto i_c) {
+          TAW_CONST(i, i_c);
+          if constexpr (i + kA < 8) rd(std::integral_constant<int, i + kA>{});
+          __builtin_amdgcn_sched_barrier(0);
+          sacc = mfma(fq[i], fk[i], sacc);
+          pacc = mfma(fo[i], vf[i], pacc);
+          __builtin_amdgcn_sched_barrier(0);
         });
         __builtin_amdgcn_s_setprio(0);
-        if (qrow0 < kv0w + 31) {                         // block crosses the diagonal (wavefront-uniform): invisible pairs get score -inf
-          asm volatile("" ::: "memory");                 // keeps this a branch: most blocks skip the compares
+        if (qrow0 < kv0w + 31) {
+          asm volatile("" ::: "memory");
 #pragma unroll
           for (int r = 0; r < 16; ++r) {
             const int qi = qrow0 + 8 * (r >> 2) + 4 * hh + (r & 3);
@@ -603,57 +623,47 @@ attn_bwd_dkv_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ d
         }
 #pragma unroll
         for (int r4 = 0; r4 < 4; ++r4) {
-          const f32x4_t l4 = *reinterpret_cast<lds_f4_t>(sl + (qb * 32 + 8 * r4) * 4);     // +inf for rows beyond S: p = 0
-#pragma unroll
-          for (int e = 0; e < 4; ++e) sacc[4 * r4 + e] = fast_exp2(__builtin_fmaf(sacc[4 * r4 + e], c, -l4[e]));
-        }
-#pragma unroll
-        for (int tt = 0; tt < 2; ++tt) pb[tt] = pack8(sacc, tt);
-      }
-      {
-        f32x16_t pacc;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) pacc[r] = 0.f;
-        __builtin_amdgcn_s_setprio(1);
-        static_for<8>([&](auto ks_c) {
-          TAW_CONST(ks, ks_c);
-          pacc = mfma(frag_nat2<ks, kTileBytes + qb * 8192, true>(nat_t), vf[ks], pacc);
-        });
-        __builtin_amdgcn_s_setprio(0);
-#pragma unroll
-        for (int r4 = 0; r4 < 4; ++r4) {
+          const f32x4_t l4 = *reinterpret_cast<lds_f4_t>(sl + (qb * 32 + 8 * r4) * 4);
           const f32x4_t d4 = *reinterpret_cast<lds_f4_t>(sl + (BQ + qb * 32 + 8 * r4) * 4);
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
             const int r = 4 * r4 + e;
-            pacc[r] = (float)pb[r >> 3][r & 7] * (pacc[r] - d4[e]);
+            const float pr = fast_exp2(__builtin_fmaf(sacc[r], c, -l4[e]));
+            sacc[r] = pr;
+            pacc[r] = pr * (pacc[r] - d4[e]);
           }
         }
 #pragma unroll
-        for (int tt = 0; tt < 2; ++tt) dsb[tt] = pack8(pacc, tt);
+        for (int tt = 0; tt < 2; ++tt) { pb[tt] = pack8(sacc, tt); dsb[tt] = pack8(pacc, tt); }
       }
-      __builtin_amdgcn_s_setprio(1);
-      static_for<4>([&](auto dt_c) {
-        TAW_CONST(dt, dt_c);
-        static_for<2>([&](auto tt_c) {
-          TAW_CONST(tt, tt_c);
-          bf16x8_t fq, fdo;
-          frag_tr2x2<tt, dt, qb * 8192, kTileBytes + qb * 8192, true>(tr_t, fq, fdo);
-          dv[dt] = mfma(fdo, pb[tt], dv[dt]);
-          dk[dt] = mfma(fq, dsb[tt], dk[dt]);
+      {
+        bf16x8_t fq[8], fdo[8];
+        auto rd = [&](auto i_c) {
+          TAW_CONST(i, i_c);
+          frag_tr2x2<i % 2, i / 2, qb * 8192, kTileBytes + qb * 8192, true>(tr_t, fq[i], fdo[i]);
+        };
+        static_for<kA>(rd);
+        __builtin_amdgcn_s_setprio(1);
+        static_for<8>([&](auto i_c) {
+          TAW_CONST(i, i_c);
+          if constexpr (i + kA < 8) rd(std::integral_constant<int, i + kA>{});
+          __builtin_amdgcn_sched_barrier(0);
+          dv[i / 2] = mfma(fdo[i], pb[i % 2], dv[i / 2]);
+          dk[i / 2] = mfma(fq[i], dsb[i % 2], dk[i / 2]);
+          __builtin_amdgcn_sched_barrier(0);
         });
-      });
-      __builtin_amdgcn_s_setprio(0);
+        __builtin_amdgcn_s_setprio(0);
+      }
     });
   }
-  __syncthreads();          // the ring becomes the output staging area
+  __syncthreads();
 
   bf16_t* stage = reinterpret_cast<bf16_t*>(lds_raw) + wave * (32 * 136);
   bf16_t* dkout = dqkv + (int64_t)b * S * ld + H + (int64_t)h * D;
   bf16_t* dvout = dkout + H;
-  if (rope) {                                          // k was rotated: its gradient goes back through the rotation
+  if (rope) {
     int ln = lane;
-    asm volatile("" : "+v"(ln));                       // table addresses are made here, not kept in registers through the loop
+    asm volatile("" : "+v"(ln));
     rope_inverse_T(dk, rope, kv0w + (ln & 31), S, ln);
   }
   store_rows_T(dk, scale, stage, dkout, ld, kv0w, S, lane);
@@ -1273,7 +1283,7 @@ int launch_attn_bwd_mfma(int B, int S, int nh, const void* qkv, const void* o, c
     return (int)hipGetLastError();
   }
   {
-    constexpr size_t lds = 4 * (2 * kTileBytes + 2 * 64 * sizeof(float));
+    constexpr size_t lds = kKvLds;
     static_assert(lds >= 8 * 32 * 136 * sizeof(bf16_t), "staging area");
     TAW_SET_LDS_LIMIT_ONCE(attn_bwd_dkv_kernel, lds);
     const int nkt = (S + 255) / 256;
