@@ -62,6 +62,8 @@ PEAK_HBM_GBS = 8000.0
 # separate profiler invocation, not part of a timed run.  (workload, kernel) -> (bytes, file under profiles/ it comes from)
 TRAFFIC_BYTES_PER_LAUNCH = {
     ("C2", "gemm"): (1459.7e6, "profiles/gemm_C2_hbm_traffic.md"),
+    ("C3", "gemm"): (5605.0e6, "profiles/attn_C3_kernels.md"),
+    ("C3", "attn_bwd"): (15.97e9, "profiles/attn_C3_kernels.md"),
 }
 # the paper's throughput table (Experiments, Throughput and Memory Usage): micro-batch size per sequence length and
 # TawPipe's tokens per GPU per second on its own hardware
@@ -351,6 +353,13 @@ def run_layer_workload(env, cfg, steps, warmup, kernel_leg=True, recompute_leg=T
         scr = torch.empty(taw.taw_op_attn_bwd_scratch_floats(cfg.B, cfg.S, cfg.n_heads), dtype=torch.float32, device="cuda")
         tf = ev_time(lambda: taw.taw_op_attn_fwd(BF, cfg.B, cfg.S, cfg.n_heads, cfg.head_dim, qkv, o, lse, taw.TAW_IMPL_MFMA, compute), 3)
         tb = ev_time(lambda: taw.taw_op_attn_bwd(BF, cfg.B, cfg.S, cfg.n_heads, cfg.head_dim, qkv, o, dO, lse, dqkv, scr, rope, taw.TAW_IMPL_MFMA, compute), 3)
+        # the two other forms of the backward (one kernel, 5 products: dQ partial sums in private slots / fp32 atomics), for the record
+        scr_all = scr
+        forms = {"split (default: dK/dV kernel + dQ kernel, 7 products)": round(tb, 4)}
+        for fname, impl in (("fused, dQ slots (5 products, no atomics)", taw.TAW_IMPL_MFMA_FUSED), ("fused, fp32 atomics (5 products)", taw.TAW_IMPL_MFMA_ATOMIC)):
+            tt_ = ev_time(lambda: taw.taw_op_attn_bwd(BF, cfg.B, cfg.S, cfg.n_heads, cfg.head_dim, qkv, o, dO, lse, dqkv, scr_all, rope, impl, compute), 2)
+            forms[fname] = round(tt_, 4)
+        kernels["attn_bwd_forms_ms"] = forms
         kernels["attn_fwd"] = {"ms": round(tf, 4), "model_TFLOPs": round(attn_fl / 3 / tf / 1e9, 1)}
         kernels["attn_bwd"] = {"ms": round(tb, 4), "model_TFLOPs": round(attn_fl * 2 / 3 / tb / 1e9, 1)}
         prod = attn_fl / 6.0                   # one S x S x d product over the causal pairs

@@ -100,6 +100,15 @@ def test_bf16_layer_on_mfma_kernels(taw, B, S, nh, I_, sigma):
     U.check_layer(taw, cfg, seed=B + S, gamma_jitter=0.1)
 
 
+@pytest.mark.parametrize("H,nh,B,S", [(1024, 8, 4, 512), (2048, 16, 2, 384)])
+def test_bf16_layer_at_the_widths_of_the_papers_throughput_table(taw, H, nh, B, S):
+    """The narrower models of the paper's throughput table (Experiments, Throughput and Memory Usage: H = 1024 and 2048,
+    heads of 128, I = 8H/3 rounded up to 256, micro-batches of several sequences): whole layer against the oracle, every
+    element, at a reduced sequence length."""
+    cfg = I.LayerConfig(f"table-{H}", I.BF16, B, S, H, nh, 128, (8 * H // 3 + 255) // 256 * 256)
+    U.check_layer(taw, cfg, seed=H + S)
+
+
 def test_bf16_layer_with_the_fused_attention_backward(taw):
     """TAW_ATTN_BWD_FUSED: the layer's backward with the one-kernel attention backward (dQ partial sums in private
     slots inside the workspace) against the oracle, and against the default pair of kernels (same tolerance; the two
