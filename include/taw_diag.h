@@ -49,6 +49,12 @@ int taw_diag_lds_read_rate(int32_t instr, int32_t waves, double* bytes_per_clock
  * (what a private slot allows).  buf: S * n_heads * 128 floats (overwritten).  *updates_per_s counts 4-byte elements. */
 int taw_diag_dq_update_rate(float* buf, int32_t S, int32_t n_heads, int32_t mode, double* updates_per_s, double* ms);
 
+/* The order in which the GEMM kernels' grid walks its 256 x 256 output tiles, evaluated on the host (no GPU call):
+ * workgroup id b of a grid of tiles_m x tiles_n tiles computes tile (tile_rows[b], tile_cols[b]).  Host arrays of
+ * tiles_m * tiles_n int32 each.  Ids b and b + 8 k run on one XCD, ids of one block of 256 at about the same time;
+ * the tests check that the map is a bijection for ragged grids and count the operand panels such a block shares. */
+int taw_diag_gemm_tile_order(int32_t tiles_m, int32_t tiles_n, int32_t* tile_rows, int32_t* tile_cols);
+
 #ifdef __cplusplus
 }
 #endif

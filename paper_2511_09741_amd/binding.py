@@ -75,6 +75,7 @@ _SIGS = {
     "taw_diag_mfma_loop": (C.c_int, [_i32, _i32, _vp, _sz, C.POINTER(taw_diag_rate)]),
     "taw_diag_lds_read_rate": (C.c_int, [_i32, _i32, C.POINTER(C.c_double), C.POINTER(C.c_double)]),
     "taw_diag_dq_update_rate": (C.c_int, [_vp, _i32, _i32, _i32, C.POINTER(C.c_double), C.POINTER(C.c_double)]),
+    "taw_diag_gemm_tile_order": (C.c_int, [_i32, _i32, C.POINTER(C.c_int32), C.POINTER(C.c_int32)]),
     "taw_status_string": (C.c_char_p, [C.c_int]),
     "taw_last_error": (C.c_char_p, []),
     "taw_op_gemm": (C.c_int, [_i32, _i32, _i64, _i64, _i64, _vp, _i64, _vp, _i64, _vp, _i64, _i32, _i32, _vp, _i64, _i32, _vp]),
@@ -319,3 +320,11 @@ def taw_diag_dq_update_rate(buf, S, n_heads, mode) -> dict:
     a, b = C.c_double(), C.c_double()
     _check(load().taw_diag_dq_update_rate(_p(buf), S, n_heads, mode, C.byref(a), C.byref(b)))
     return {"updates_per_s": a.value, "ms": b.value}
+
+
+def taw_diag_gemm_tile_order(tiles_m, tiles_n):
+    """(rows, cols): lists with the output tile of every workgroup id of a tiles_m x tiles_n GEMM grid.  Host only."""
+    n = max(int(tiles_m) * int(tiles_n), 1)
+    rows, cols = (C.c_int32 * n)(), (C.c_int32 * n)()
+    _check(load().taw_diag_gemm_tile_order(tiles_m, tiles_n, rows, cols))
+    return list(rows), list(cols)

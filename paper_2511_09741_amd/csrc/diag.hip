@@ -4,6 +4,7 @@
 
 #include "../../include/taw_diag.h"
 #include "dev_common.h"
+#include "taw_internal.h"
 
 namespace taw {
 namespace {
@@ -266,5 +267,17 @@ extern "C" int taw_diag_dq_update_rate(float* buf, int32_t S, int32_t n_heads, i
   elems *= n_heads;
   *updates_per_s = elems / ((double)ms * 1e-3);
   *ms_out = ms;
+  return TAW_OK;
+}
+
+extern "C" int taw_diag_gemm_tile_order(int32_t tiles_m, int32_t tiles_n, int32_t* tile_rows, int32_t* tile_cols) {
+  if (tiles_m < 1 || tiles_n < 1 || (int64_t)tiles_m * tiles_n > (1 << 24)) return TAW_ERR_SHAPE;
+  if (!tile_rows || !tile_cols) return TAW_ERR_NULL;
+  for (int b = 0; b < tiles_m * tiles_n; ++b) {
+    int tm, tn;
+    taw::gemm_tile_of_block(b, tiles_m, tiles_n, &tm, &tn);
+    tile_rows[b] = tm;
+    tile_cols[b] = tn;
+  }
   return TAW_OK;
 }

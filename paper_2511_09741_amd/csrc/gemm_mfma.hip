@@ -19,9 +19,9 @@
 // ds_read_b64_tr_b16, which hands each lane 4 consecutive k of one column: the transposition the
 // MFMA operand layout needs happens in the LDS read, not in a separate pass over HBM.
 //
-// Workgroup ids are remapped so that the 8 XCDs (ids are dealt round-robin to them) each work on a
-// contiguous band of tiles and, inside a band, on groups of 8 tile rows: tiles that share an
-// operand panel then share one XCD's L2.
+// Workgroup ids are remapped (gemm_tile_of_block) so that the 32 tiles an XCD works on at a time are an 8 x 4
+// block sharing operand panels in that XCD's L2, and the 256 tiles of the whole chip about a 16 x 16 block
+// sharing them in the memory-side cache.
 #include <type_traits>
 
 #include "dev_common.h"
@@ -148,17 +148,8 @@ gemm_mfma_kernel(int64_t M, int64_t N, int64_t K, const bf16_t* __restrict__ A, 
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   // ---- XCD-aware tile id
-  const int ntiles = tiles_m * tiles_n;
-  int pid = blockIdx.x;
-  const int n8 = ntiles & ~7;
-  if (pid < n8) pid = (pid & 7) * (n8 >> 3) + (pid >> 3);
-  constexpr int GROUP = 8;
-  const int per_group = GROUP * tiles_n;
-  const int g = pid / per_group;
-  const int gm0 = g * GROUP;
-  const int gsize = (tiles_m - gm0) < GROUP ? (tiles_m - gm0) : GROUP;
-  const int tm = gm0 + (pid % per_group) % gsize;
-  const int tn = (pid % per_group) / gsize;
+  int tm, tn;
+  gemm_tile_of_block((int)blockIdx.x, tiles_m, tiles_n, &tm, &tn);
   const int64_t m0 = (int64_t)tm * BM, n0 = (int64_t)tn * BN;
 
   TileLoader<A_KC> la;
@@ -602,18 +593,9 @@ __device__ __forceinline__ void gemm_dlds_body(const GemmArgs& ga, int block) {
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  // ---- XCD-aware tile id (see file header)
-  const int ntiles = tiles_m * tiles_n;
-  int pid = block;
-  const int n8 = ntiles & ~7;
-  if (pid < n8) pid = (pid & 7) * (n8 >> 3) + (pid >> 3);
-  constexpr int GROUP = 8;
-  const int per_group = GROUP * tiles_n;
-  const int g = pid / per_group;
-  const int gm0 = g * GROUP;
-  const int gsize = (tiles_m - gm0) < GROUP ? (tiles_m - gm0) : GROUP;
-  const int tm = gm0 + (pid % per_group) % gsize;
-  const int tn = (pid % per_group) / gsize;
+  // ---- XCD-aware tile id
+  int tm, tn;
+  gemm_tile_of_block(block, tiles_m, tiles_n, &tm, &tn);
   const int64_t m0 = (int64_t)tm * BM, n0 = (int64_t)tn * BN;
 
   const int wm = (wave >> 1) * 128, wn = (wave & 1) * 128;
@@ -795,18 +777,9 @@ __device__ __forceinline__ void gemm_dlds64_body(const GemmArgs& ga, int block) 
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  // ---- XCD-aware tile id (see file header)
-  const int ntiles = tiles_m * tiles_n;
-  int pid = block;
-  const int n8 = ntiles & ~7;
-  if (pid < n8) pid = (pid & 7) * (n8 >> 3) + (pid >> 3);
-  constexpr int GROUP = 8;
-  const int per_group = GROUP * tiles_n;
-  const int g = pid / per_group;
-  const int gm0 = g * GROUP;
-  const int gsize = (tiles_m - gm0) < GROUP ? (tiles_m - gm0) : GROUP;
-  const int tm = gm0 + (pid % per_group) % gsize;
-  const int tn = (pid % per_group) / gsize;
+  // ---- XCD-aware tile id
+  int tm, tn;
+  gemm_tile_of_block(block, tiles_m, tiles_n, &tm, &tn);
   const int64_t m0 = (int64_t)tm * BM, n0 = (int64_t)tn * BN;
 
   const int wm = (wave >> 1) * 128, wn = (wave & 1) * 128;

@@ -64,6 +64,40 @@ int launch_attn_fwd_generic(int dtype, int B, int S, int nh, int d, const void* 
 int launch_attn_bwd_generic(int dtype, int B, int S, int nh, int d, const void* qkv, const void* dO,
                             const float* lse, const float* D, void* dqkv, hipStream_t st);
 
+// ---- order in which a GEMM grid walks its 256 x 256 output tiles ------------------------------
+// Workgroup ids are dealt round-robin to the 8 XCDs (32 compute units and one 4 MiB L2 each), and each XCD
+// starts its ids in order, so the ids [256 r, 256 r + 256) run at about the same time ("round" r) and id b
+// of a round runs on XCD b % 8.  Tiles are laid along one locality-preserving sequence: super-tiles of
+// 16 x 16 tiles (tile rows outer, the super-tiles of 16 rows side by side inner), each made of two halves of
+// 8 rows, each half walked in groups of 4 columns, rows fastest.  Position p of that sequence goes to
+// round p / 256, XCD (p / 32) % 8: a round then covers about one super-tile, so the whole chip streams 16 + 16
+// operand panels per 256 tiles through the memory-side cache (a band of tile rows per XCD streams 64 + 4),
+// and an XCD's 32 concurrent tiles are still an 8 x 4 block that shares panels in its own L2.
+// The map is a bijection from [0, tiles_m * tiles_n) onto the tiles for every grid shape; ragged edges only
+// shift where the blocks fall.  Host code can evaluate it too (the tests do).
+__host__ __device__ inline void gemm_tile_of_block(int block, int tiles_m, int tiles_n, int* tm, int* tn) {
+  const int ntiles = tiles_m * tiles_n;
+  const int n256 = ntiles & ~255;
+  int p = block;
+  if (block < n256) {
+    p = (block & ~255) + (block & 7) * 32 + ((block >> 3) & 31);
+  } else {                                      // last, partial round: every XCD takes one run of the sequence
+    const int t = block - n256, n8 = (ntiles - n256) & ~7;
+    if (t < n8) p = n256 + (t & 7) * (n8 >> 3) + (t >> 3);
+  }
+  const int per_sr = 16 * tiles_n;              // tiles in a full super-row
+  const int R = p / per_sr, p1 = p - R * per_sr;
+  const int hR = tiles_m - 16 * R < 16 ? tiles_m - 16 * R : 16;
+  const int C = p1 / (hR * 16), p2 = p1 - C * (hR * 16);
+  const int wC = tiles_n - 16 * C < 16 ? tiles_n - 16 * C : 16;
+  const int ht = hR < 8 ? hR : 8, top = ht * wC;
+  const bool lower = p2 >= top;
+  const int h = lower ? hR - 8 : ht, q = lower ? p2 - top : p2;
+  const int cg = q / (4 * h), q2 = q - cg * (4 * h);
+  *tm = 16 * R + (lower ? 8 : 0) + q2 % h;
+  *tn = 16 * C + 4 * cg + q2 / h;
+}
+
 // ---- MFMA bf16 kernels (gemm_mfma.hip, attn_mfma.hip) -----------------------------------------
 bool gemm_mfma_supported(int dtype, int mode, int64_t M, int64_t N, int64_t K, int64_t lda, int64_t ldb,
                          int64_t ldc, int c_dtype, int64_t ldr);

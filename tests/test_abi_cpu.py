@@ -31,7 +31,7 @@ def declared_functions():
 
 def test_every_declared_symbol_is_exported(lib):
     names = declared_functions()
-    assert len(names) == 32
+    assert len(names) == 33
     for n in names:
         assert hasattr(lib, n), f"{n} declared in include/ but not exported"
     assert set(names) == set(taw.EXPORTS)
@@ -218,6 +218,35 @@ def test_diag_validation(lib):
     assert e.value.status == taw.TAW_ERR_SHAPE
     with pytest.raises(taw.TawError) as e:
         taw.taw_diag_dq_update_rate(0x10000, 1000, 32, 0)            # S must be a multiple of 256
+    assert e.value.status == taw.TAW_ERR_SHAPE
+
+
+@pytest.mark.parametrize("tiles_m,tiles_n", [(1, 1), (3, 5), (16, 16), (17, 19), (7, 300), (300, 7), (33, 33), (128, 48), (128, 86), (86, 16), (16, 43), (32, 8)])
+def test_gemm_tile_order_is_a_bijection_that_keeps_concurrent_tiles_together(lib, tiles_m, tiles_n):
+    rows, cols = taw.taw_diag_gemm_tile_order(tiles_m, tiles_n)
+    n = tiles_m * tiles_n
+    assert len(rows) == n and sorted(zip(rows, cols)) == [(r, c) for r in range(tiles_m) for c in range(tiles_n)]
+    # ids of one block of 256 run at about the same time, id b on XCD b % 8: count the distinct operand panels
+    # (tile rows + tile columns) each full block touches, chip-wide and per XCD
+    per_xcd = []
+    for r0 in range(0, n - 255, 256):
+        blk = range(r0, r0 + 256)
+        chip = len({rows[b] for b in blk}) + len({cols[b] for b in blk})
+        assert chip <= 64, (r0, chip)          # a 16 x 16 block has 32; ragged edges split a block over up to 3 pieces
+        for x in range(8):
+            mine = [b for b in blk if b % 8 == x]
+            per_xcd.append(len({rows[b] for b in mine}) + len({cols[b] for b in mine}))
+    if per_xcd:                                # 8 x 4 has 12; a block that straddles a ragged edge has more
+        assert sum(per_xcd) / len(per_xcd) <= 16 and max(per_xcd) <= 40, (max(per_xcd), sum(per_xcd) / len(per_xcd))
+    if tiles_m % 16 == 0 and tiles_n % 16 == 0:
+        for r0 in range(0, n, 256):
+            blk = range(r0, r0 + 256)
+            assert len({rows[b] for b in blk}) == 16 and len({cols[b] for b in blk}) == 16
+            for x in range(8):
+                mine = [b for b in blk if b % 8 == x]
+                assert len({rows[b] for b in mine}) == 8 and len({cols[b] for b in mine}) == 4
+    with pytest.raises(taw.TawError) as e:
+        taw.taw_diag_gemm_tile_order(0, 4)
     assert e.value.status == taw.TAW_ERR_SHAPE
 
 
