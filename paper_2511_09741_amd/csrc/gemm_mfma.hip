@@ -192,7 +192,7 @@ gemm_mfma_kernel(int64_t M, int64_t N, int64_t K, const bf16_t* __restrict__ A, 
 #pragma unroll
       for (int i = 0; i < 4; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+        for (int j = 0; j < 4; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);     // block (i, j) transposed, see stage_rows
     }
     if (more) {
       bf16_t* da = lds + ((kt + 1) & 1) * kStageElems;
@@ -202,18 +202,19 @@ gemm_mfma_kernel(int64_t M, int64_t N, int64_t K, const bf16_t* __restrict__ A, 
     __syncthreads();
   }
 
-  // ---- epilogue: accumulator register r of lane l is C[row0 + 8 (r/4) + 4 (l>>5) + r%4][col0 + (l&31)]
-  const int lcol = lane & 31, lrow = 4 * (lane >> 5);
+  // ---- epilogue: the blocks are transposed (see stage_rows): accumulator register r of lane l is
+  // C[row0 + (l&31)][col0 + 8 (r/4) + 4 (l>>5) + r%4]
+  const int lrow = lane & 31, lcol = 4 * (lane >> 5);
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
+    const int64_t row = m0 + wm + 32 * i + lrow;
+    if (row >= M) continue;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-      const int64_t col = n0 + wn + 32 * j + lcol;
-      if (col >= N) continue;
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        const int64_t row = m0 + wm + 32 * i + 8 * (r >> 2) + lrow + (r & 3);
-        if (row >= M) continue;
+        const int64_t col = n0 + wn + 32 * j + 8 * (r >> 2) + lcol + (r & 3);
+        if (col >= N) continue;
         float v = acc[i][j][r];
         if (C_F32) {
           float* C = static_cast<float*>(Cv);
@@ -355,6 +356,19 @@ __device__ constexpr int kMfmaI[16] = {0, 0, 1, 1, 0, 1, 2, 2, 2, 0, 1, 2, 3, 3,
 __device__ constexpr int kMfmaJ[16] = {0, 1, 0, 1, 2, 2, 0, 1, 2, 3, 3, 3, 0, 1, 2, 3};
 __device__ constexpr int kReadOrder[8] = {0, 4, 5, 1, 6, 2, 7, 3};
 
+// ---- accumulator block -> staging rows.  The MFMAs multiply (B fragment) x (A fragment)^T, so a 32 x 32 block of
+// the result sits transposed in the accumulator registers: lane l holds ROW l & 31 of the block and, in registers
+// 4 g .. 4 g + 3, the four consecutive COLUMNS 8 g + 4 (l >> 5) + 0..3.  Four consecutive floats of a row are one
+// 16-byte LDS write: a block goes to the fp32 staging rows ([32][SLD], SLD * 4 a multiple of 16) in 4 writes per lane
+// instead of the 16 single-float writes the untransposed layout (a lane = a column) needs.
+template <int SLD>
+__device__ __forceinline__ void stage_rows(const f32x16_t& blk, float* stg_blk, int lane) {
+  float* row = stg_blk + (lane & 31) * SLD + 4 * (lane >> 5);
+#pragma unroll
+  for (int g = 0; g < 4; ++g)
+    *reinterpret_cast<f32x4_t*>(row + 8 * g) = f32x4_t{blk[4 * g], blk[4 * g + 1], blk[4 * g + 2], blk[4 * g + 3]};
+}
+
 // ---- the same for a tile that lies wholly inside C with 16-byte aligned row segments (all tiles of
 // the layer's shapes): no per-element checks, 32-bit lane offsets from the wavefront's corner of C
 // The result is stored non-temporally: a round of tiles writes more than an L2 holds, and ordinary stores
@@ -378,7 +392,6 @@ __device__ __forceinline__ void store_tile_full(const f32x16_t (&acc)[4][4], uns
   constexpr int SLD = 132;
   constexpr int ES = C_F32 ? 4 : 2;                       // bytes per element of C (and R)
   float* stg = reinterpret_cast<float*>(lds2) + wave * (32 * SLD);
-  const int lcol = lane & 31, lrow = 4 * (lane >> 5);
   char* cw = static_cast<char*>(Cv) + ((m0 + wm) * ldc + n0 + wn) * ES;
   const char* rw = Rv ? static_cast<const char*>(Rv) + ((m0 + wm) * ldr + n0 + wn) * ES : nullptr;
   // read-back: a lane takes 16 bytes of a row; C_F32: 32 lanes per row (2 rows per pass), else 16 lanes per row (4 rows per pass)
@@ -390,9 +403,7 @@ __device__ __forceinline__ void store_tile_full(const f32x16_t (&acc)[4][4], uns
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
 #pragma unroll
-    for (int j = 0; j < 4; ++j)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) stg[(8 * (r >> 2) + lrow + (r & 3)) * SLD + 32 * j + lcol] = acc[i][j][r];
+    for (int j = 0; j < 4; ++j) stage_rows<SLD>(acc[i][j], stg + 32 * j, lane);
     __builtin_amdgcn_s_waitcnt(0xc07f);
     __builtin_amdgcn_wave_barrier();
     char* ci = cw + (int64_t)(32 * i) * ldc * ES;
@@ -466,7 +477,6 @@ __device__ __forceinline__ void store_tile(const f32x16_t (&acc)[4][4], unsigned
       return;
     }
   }
-  const int lcol = lane & 31, lrow = 4 * (lane >> 5);
   if (C_F32) {
     float* C = static_cast<float*>(Cv);
     const float* R = static_cast<const float*>(Rv);
@@ -476,9 +486,7 @@ __device__ __forceinline__ void store_tile(const f32x16_t (&acc)[4][4], unsigned
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
 #pragma unroll
-      for (int j = 0; j < 4; ++j)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) stg[(8 * (r >> 2) + lrow + (r & 3)) * SLD + 32 * j + lcol] = acc[i][j][r];
+      for (int j = 0; j < 4; ++j) stage_rows<SLD>(acc[i][j], stg + 32 * j, lane);
       __builtin_amdgcn_s_waitcnt(0xc07f);
       __builtin_amdgcn_wave_barrier();
       // 32 rows x 128 cols = 1024 chunks of 4 columns; lane -> (row = idx >> 5, chunk = idx & 31): half a
@@ -516,9 +524,7 @@ __device__ __forceinline__ void store_tile(const f32x16_t (&acc)[4][4], unsigned
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
 #pragma unroll
-      for (int j = 0; j < 4; ++j)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) stg[(8 * (r >> 2) + lrow + (r & 3)) * SLD + 32 * j + lcol] = acc[i][j][r];
+      for (int j = 0; j < 4; ++j) stage_rows<SLD>(acc[i][j], stg + 32 * j, lane);
       __builtin_amdgcn_s_waitcnt(0xc07f);
       __builtin_amdgcn_wave_barrier();
       // 32 rows x 128 cols = 512 chunks of 8 columns; lane -> (row = idx >> 4, chunk = idx & 15)
@@ -639,7 +645,7 @@ __device__ __forceinline__ void gemm_dlds_body(const GemmArgs& ga, int block) {
   // that ended the previous step) and the fragment reads of k-step 1.  Second half: MFMAs of
   // k-step 1 with the first fragments of tile kt + 1 (visible since the previous barrier).
   auto constexpr_mfma = [&](int e, int h) {
-    acc[kMfmaI[e]][kMfmaJ[e]] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[h][kMfmaI[e]], fb[h][kMfmaJ[e]], acc[kMfmaI[e]][kMfmaJ[e]], 0, 0, 0);
+    acc[kMfmaI[e]][kMfmaJ[e]] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[h][kMfmaJ[e]], fa[h][kMfmaI[e]], acc[kMfmaI[e]][kMfmaJ[e]], 0, 0, 0);
   };
   auto step = [&](int kt, auto load_c) {
     constexpr bool LOAD = decltype(load_c)::value;
@@ -822,7 +828,7 @@ __device__ __forceinline__ void gemm_dlds64_body(const GemmArgs& ga, int block) 
     fb[0][i] = ob.frag(lds + kOp64, i, 0);
   }
   auto constexpr_mfma = [&](int e, int h) {
-    acc[kMfmaI[e]][kMfmaJ[e]] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[h][kMfmaI[e]], fb[h][kMfmaJ[e]], acc[kMfmaI[e]][kMfmaJ[e]], 0, 0, 0);
+    acc[kMfmaI[e]][kMfmaJ[e]] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[h][kMfmaJ[e]], fa[h][kMfmaI[e]], acc[kMfmaI[e]][kMfmaJ[e]], 0, 0, 0);
   };
   // one K step of 64.  LB: the B half of stage kt + 1 is still to be loaded (during q0); LA: stage
   // kt + 2 exists, its A half is loaded during q3 into the stage this step has finished with;
