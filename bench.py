@@ -570,7 +570,19 @@ def run_diag(env):
     src.view(torch.int32).random_(0, 1 << 30)
     names = {taw.TAW_DIAG_MFMA_RANDOM: "mfma_only_random_operands", taw.TAW_DIAG_MFMA_ZERO: "mfma_only_zero_operands",
              taw.TAW_DIAG_MFMA_LDS: "mfma_plus_lds_fragment_reads", taw.TAW_DIAG_MFMA_LDS_LOADS: "mfma_plus_lds_reads_plus_global_to_lds_loads"}
-    out = {"mfma_loop": {}, "lds_read_bytes_per_clock_per_cu": {}, "dq_update": {}, "gemm_by_tiles": []}
+    out = {"mfma_loop": {}, "lds_read_bytes_per_clock_per_cu": {}, "issue_cycles_per_mfma_slot": {}, "dq_update": {}, "gemm_by_tiles": []}
+    # vector instructions beside MFMAs: cycles per slot of {1 MFMA + n vector instructions} (32 = the matrix pipe never idles)
+    mode_names = ("one wavefront per SIMD, interleaved", "two wavefronts per SIMD, each interleaved (64 = pipe never idles)",
+                  "two wavefronts per SIMD, one MFMAs only, one vector instructions only")
+    for mode, mname in enumerate(mode_names):
+        for kind, kname in enumerate(("v_fma_f32", "v_exp_f32")):
+            for n in (0, 2, 4, 8):
+                if n == 0 and kind == 1:
+                    continue
+                r = taw.taw_diag_issue_rate(mode, kind, n)
+                key = f"{mname}; {n} x {kname}" if n else f"{mname}; MFMAs only"
+                out["issue_cycles_per_mfma_slot"][key] = {"mfma_wavefront": round(r["cycles_per_slot_mfma_wave"], 1),
+                                                            "last_wavefront": round(r["cycles_per_slot_last_wave"], 1)}
     for kind, name in names.items():
         r = taw.taw_diag_mfma_loop(kind, 20000, src)
         out["mfma_loop"][name] = {k: round(v, 3) for k, v in r.items()}

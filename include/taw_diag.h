@@ -49,6 +49,15 @@ int taw_diag_lds_read_rate(int32_t instr, int32_t waves, double* bytes_per_clock
  * (what a private slot allows).  buf: S * n_heads * 128 floats (overwritten).  *updates_per_s counts 4-byte elements. */
 int taw_diag_dq_update_rate(float* buf, int32_t S, int32_t n_heads, int32_t mode, double* updates_per_s, double* ms);
 
+/* How vector instructions issue beside MFMAs on one SIMD: core-clock cycles per slot of {one MFMA + nvalu vector instructions}.
+ * mode 0: one wavefront per SIMD runs both; mode 1: two wavefronts per SIMD, each runs both; mode 2: two wavefronts per SIMD,
+ * one issues only the MFMAs, the other only the vector instructions.  kind 0: v_fma_f32, 1: v_exp_f32.  nvalu: 0, 2, 4 or 8.
+ * *cycles_mfma_wave: per slot, seen by a wavefront that issues MFMAs (32 = the matrix pipe never idles with one such
+ * wavefront per SIMD, 64 with two); *cycles_valu_wave: the same for the last wavefront (the vector-only one in mode 2).
+ * What the attention kernels' design rests on: a lone wavefront issues about one vector instruction per 5 cycles, two
+ * wavefronts of a SIMD issue theirs side by side. */
+int taw_diag_issue_rate(int32_t mode, int32_t kind, int32_t nvalu, double* cycles_mfma_wave, double* cycles_valu_wave);
+
 /* The order in which the GEMM kernels' grid walks its 256 x 256 output tiles, evaluated on the host (no GPU call):
  * workgroup id b of a grid of tiles_m x tiles_n tiles computes tile (tile_rows[b], tile_cols[b]).  Host arrays of
  * tiles_m * tiles_n int32 each.  Ids b and b + 8 k run on one XCD, ids of one block of 256 at about the same time;

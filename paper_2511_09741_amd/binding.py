@@ -76,6 +76,7 @@ _SIGS = {
     "taw_diag_lds_read_rate": (C.c_int, [_i32, _i32, C.POINTER(C.c_double), C.POINTER(C.c_double)]),
     "taw_diag_dq_update_rate": (C.c_int, [_vp, _i32, _i32, _i32, C.POINTER(C.c_double), C.POINTER(C.c_double)]),
     "taw_diag_gemm_tile_order": (C.c_int, [_i32, _i32, C.POINTER(C.c_int32), C.POINTER(C.c_int32)]),
+    "taw_diag_issue_rate": (C.c_int, [_i32, _i32, _i32, C.POINTER(C.c_double), C.POINTER(C.c_double)]),
     "taw_status_string": (C.c_char_p, [C.c_int]),
     "taw_last_error": (C.c_char_p, []),
     "taw_op_gemm": (C.c_int, [_i32, _i32, _i64, _i64, _i64, _vp, _i64, _vp, _i64, _vp, _i64, _i32, _i32, _vp, _i64, _i32, _vp]),
@@ -328,3 +329,9 @@ def taw_diag_gemm_tile_order(tiles_m, tiles_n):
     rows, cols = (C.c_int32 * n)(), (C.c_int32 * n)()
     _check(load().taw_diag_gemm_tile_order(tiles_m, tiles_n, rows, cols))
     return list(rows), list(cols)
+
+
+def taw_diag_issue_rate(mode, kind, nvalu) -> dict:
+    a, b = C.c_double(), C.c_double()
+    _check(load().taw_diag_issue_rate(mode, kind, nvalu, C.byref(a), C.byref(b)))
+    return {"cycles_per_slot_mfma_wave": a.value, "cycles_per_slot_last_wave": b.value}

@@ -144,6 +144,70 @@ __global__ void fill_zero_kernel(float* p, size_t n) {
   for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) p[i] = 0.f;
 }
 
+// ---- how vector instructions issue beside MFMAs.  Every wavefront runs `iters` trips of 4 slots; a slot is one MFMA
+// (MODE 0, 1: in every wavefront; MODE 2: in wavefronts 0..3 only) followed by NV vector instructions (MODE 0, 1: in the same
+// wavefront; MODE 2: in wavefronts 4..7, which issue no MFMA).  MODE 0 runs one wavefront per SIMD, MODE 1 and 2 two.
+// KIND 0: v_fma_f32, 1: v_exp_f32.  Core-clock ticks of the loop, per wavefront of workgroup 0, go to g_clk[wave].
+template <int KIND> __device__ __forceinline__ void issue_valu(float& x, float c) {
+  if constexpr (KIND == 0) asm volatile("v_fma_f32 %0, %0, %1, %0" : "+v"(x) : "v"(c));
+  else asm volatile("v_exp_f32 %0, %0" : "+v"(x));
+}
+template <int MODE, int KIND, int NV>
+__global__ void __launch_bounds__(512, 1) issue_kernel(int iters, float* sink) {
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  union { unsigned u[4]; bf16x8_t v; } fa, fb;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    const unsigned x = mix(threadIdx.x * 4 + e + 1), y = mix(x);
+    fa.u[e] = rnd_bf16(x) | (rnd_bf16(y) << 16);
+    fb.u[e] = rnd_bf16(y ^ 0x9e3779b9u) | (rnd_bf16(x ^ 0x85ebca6bu) << 16);
+  }
+  f32x16_t acc[4];
+#pragma unroll
+  for (int a = 0; a < 4; ++a)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[a][r] = 0.f;
+  float v[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) v[i] = 1e-3f * (float)(i + 1);
+  const float c = 1e-6f;
+  const bool do_mfma = MODE != 2 || wave < 4;                    // wavefront-uniform
+  __syncthreads();
+  const long long t0 = __builtin_readcyclecounter();
+  if (MODE != 2) {
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+      for (int a = 0; a < 4; ++a) {
+        asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc[a]) : "v"(fa.v), "v"(fb.v));
+#pragma unroll
+        for (int j = 0; j < NV; ++j) issue_valu<KIND>(v[(a * NV + j) & 7], c);
+      }
+    }
+  } else if (do_mfma) {                                          // two loops, so that neither carries the other's branches
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+      for (int a = 0; a < 4; ++a) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc[a]) : "v"(fa.v), "v"(fb.v));
+    }
+  } else {
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+      for (int a = 0; a < 4; ++a)
+#pragma unroll
+        for (int j = 0; j < NV; ++j) issue_valu<KIND>(v[(a * NV + j) & 7], c);
+    }
+  }
+  const long long t1 = __builtin_readcyclecounter();
+  float sum = 0.f;
+#pragma unroll
+  for (int a = 0; a < 4; ++a)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) sum += acc[a][r];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) sum += v[i];
+  if (sum == 123.456f) sink[threadIdx.x] = sum;                  // keeps the arithmetic alive
+  if (blockIdx.x == 0 && (threadIdx.x & 63) == 0) g_clk[wave] = t1 - t0;
+}
+
 int read_clocks(int nblocks, double* wall, double* core) {
   static long long h[2 * 256];
   hipError_t e = hipMemcpyFromSymbol(h, HIP_SYMBOL(g_clk), sizeof(long long) * 2 * nblocks);
@@ -279,5 +343,30 @@ extern "C" int taw_diag_gemm_tile_order(int32_t tiles_m, int32_t tiles_n, int32_
     tile_rows[b] = tm;
     tile_cols[b] = tn;
   }
+  return TAW_OK;
+}
+
+extern "C" int taw_diag_issue_rate(int32_t mode, int32_t kind, int32_t nvalu, double* cycles_mfma_wave, double* cycles_valu_wave) {
+  if (!cycles_mfma_wave || !cycles_valu_wave) return TAW_ERR_NULL;
+  if (mode < 0 || mode > 2 || kind < 0 || kind > 1 || (nvalu != 0 && nvalu != 2 && nvalu != 4 && nvalu != 8)) return TAW_ERR_SHAPE;
+  void* p = nullptr;
+  if (hipGetSymbolAddress(&p, HIP_SYMBOL(g_clk)) != hipSuccess) return TAW_ERR_HIP;
+  float* sink = reinterpret_cast<float*>(p) + 64;                 // 512 floats inside g_clk, behind the per-wavefront results
+  const int iters = 20000;
+  const int threads = mode == 0 ? 256 : 512;
+  float ms = 0.f;
+  int rc = -1;
+#define TAW_DIAG_ISSUE(M, K, N)                                                                                              \
+  if (mode == M && kind == K && nvalu == N) rc = timed([&] { hipLaunchKernelGGL((issue_kernel<M, K, N>), dim3(256), dim3(threads), 0, 0, iters, sink); }, &ms);
+#define TAW_DIAG_ISSUE_N(M, K) TAW_DIAG_ISSUE(M, K, 0) TAW_DIAG_ISSUE(M, K, 2) TAW_DIAG_ISSUE(M, K, 4) TAW_DIAG_ISSUE(M, K, 8)
+  TAW_DIAG_ISSUE_N(0, 0) TAW_DIAG_ISSUE_N(0, 1) TAW_DIAG_ISSUE_N(1, 0) TAW_DIAG_ISSUE_N(1, 1) TAW_DIAG_ISSUE_N(2, 0) TAW_DIAG_ISSUE_N(2, 1)
+#undef TAW_DIAG_ISSUE_N
+#undef TAW_DIAG_ISSUE
+  if (rc) return TAW_ERR_HIP;
+  long long h[8];
+  if (hipMemcpyFromSymbol(h, HIP_SYMBOL(g_clk), sizeof(h)) != hipSuccess) return TAW_ERR_HIP;
+  const double slots = (double)iters * 4;
+  *cycles_mfma_wave = (double)h[0] / slots;                         // wavefront 0 issues MFMAs in every mode
+  *cycles_valu_wave = (double)h[mode == 0 ? 3 : 7] / slots;         // the last wavefront: the vector-only one in mode 2
   return TAW_OK;
 }

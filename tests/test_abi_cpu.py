@@ -31,7 +31,7 @@ def declared_functions():
 
 def test_every_declared_symbol_is_exported(lib):
     names = declared_functions()
-    assert len(names) == 33
+    assert len(names) == 34
     for n in names:
         assert hasattr(lib, n), f"{n} declared in include/ but not exported"
     assert set(names) == set(taw.EXPORTS)
@@ -218,6 +218,12 @@ def test_diag_validation(lib):
     assert e.value.status == taw.TAW_ERR_SHAPE
     with pytest.raises(taw.TawError) as e:
         taw.taw_diag_dq_update_rate(0x10000, 1000, 32, 0)            # S must be a multiple of 256
+    assert e.value.status == taw.TAW_ERR_SHAPE
+    with pytest.raises(taw.TawError) as e:
+        taw.taw_diag_issue_rate(3, 0, 4)
+    assert e.value.status == taw.TAW_ERR_SHAPE
+    with pytest.raises(taw.TawError) as e:
+        taw.taw_diag_issue_rate(0, 0, 3)                             # 0, 2, 4 or 8 vector instructions per slot
     assert e.value.status == taw.TAW_ERR_SHAPE
 
 
