@@ -235,6 +235,13 @@ __device__ __forceinline__ void pair_tile_of_block(int blk, int npairs, int nt, 
   }
 }
 
+// max of three without the canonicalising self-maximum the compiler puts in front of fmaxf on MFMA results
+__device__ __forceinline__ float max3(float a, float b, float c) {
+  float d;
+  asm("v_max3_f32 %0, %1, %2, %3" : "=v"(d) : "v"(a), "v"(b), "v"(c));
+  return d;
+}
+
 // =============================================================================== forward
 // Workgroup: 8 wavefronts (two per SIMD, so one's softmax arithmetic overlaps the other's MFMAs),
 // one (batch, head, 256 query rows); wavefront w owns rows 32w .. 32w+31.  Keys/values stream
@@ -379,10 +386,12 @@ attn_fwd_kernel(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ o, float* _
           s[kb][r] = kv > qidx ? -INFINITY : s[kb][r];
         }
     }
-    float mx = fmaxf(s[0][0], s[1][0]);
+    // v_max3_f32 by name: fmaxf on MFMA results makes the compiler quiet possible signalling NaNs first, one extra
+    // instruction per score, and pair the maxima up with two-operand instructions (58 instructions for 32 scores instead of 16)
+    float mx = max3(s[0][0], s[1][0], s[0][0]);
 #pragma unroll
-    for (int r = 1; r < 16; ++r) mx = fmaxf(mx, fmaxf(s[0][r], s[1][r]));
-    mx = fmaxf(mx, __shfl_xor(mx, 32, 64)) * c;
+    for (int r = 1; r < 16; ++r) mx = max3(mx, s[0][r], s[1][r]);
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64)) * c;      // (v_permlane32_swap instead of this LDS round trip measured 3 % slower)
     if (__builtin_amdgcn_ballot_w64(mx > m + kMaxSlack) != 0) {    // wavefront-uniform: some row's maximum moved far
       const float m_new = fmaxf(m, mx);
       const float alpha = fast_exp2(m - m_new);        // m = -inf on the first tile: alpha = 0, the accumulators are 0
