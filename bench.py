@@ -61,9 +61,9 @@ PEAK_HBM_GBS = 8000.0
 # scaled by what the counter reads for the staging copy kernel, a plain copy of known size).  Precomputed: a counter run is a
 # separate profiler invocation, not part of a timed run.  (workload, kernel) -> (bytes, file under profiles/ it comes from)
 TRAFFIC_BYTES_PER_LAUNCH = {
-    ("C2", "gemm"): (1459.7e6, "profiles/gemm_C2_hbm_traffic.md"),
-    ("C3", "gemm"): (5605.0e6, "profiles/attn_C3_kernels.md"),
-    ("C3", "attn_bwd"): (15.97e9, "profiles/attn_C3_kernels.md"),
+    ("C2", "gemm"): (1442.9e6, "profiles/gemm_C2_hbm_traffic.md"),
+    ("C3", "gemm"): (5424.2e6, "profiles/attn_C3_kernels.md"),
+    ("C3", "attn_bwd"): (15.37e9, "profiles/attn_C3_kernels.md"),
 }
 # the paper's throughput table (Experiments, Throughput and Memory Usage): micro-batch size per sequence length and
 # TawPipe's tokens per GPU per second on its own hardware

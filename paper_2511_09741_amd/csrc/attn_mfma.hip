@@ -360,7 +360,7 @@ attn_fwd_kernel(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ o, float* _
     f32x16_t s[2];
     {
 #pragma unroll
-      for (int r = 0; r < 16; ++r) { s[0][r] = 0.f; s[1][r] = 0.f; }
+      for (int r = 0; r < 16; ++r) { s[0][r] = 0.f; s[1][r] = 0.f; }      // (folded into the first MFMA of each chain as the constant 0)
       bf16x8_t kfr[16];
       auto rd = [&](auto i_c) {
         TAW_CONST(i, i_c);
