@@ -646,9 +646,11 @@ attn_bwd_dkv_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ d
         bf16x8_t fq[8], fk[8], fo[8];
         auto rd = [&](auto i_c) {
           TAW_CONST(i, i_c);
-          fq[i] = frag_nat2<i, qb * 8192, true>(nat_t);
+          // Q and dO fragments sit at the same place of their tiles: one address for both
+          const unsigned a = xor_here<(i << 5), true>(nat_t);
+          fq[i] = *reinterpret_cast<const __attribute__((address_space(3))) bf16x8_t*>(a + qb * 8192);
           fk[i] = frag_nat2<i, 0, true>(knat_t);
-          fo[i] = frag_nat2<i, kTileBytes + qb * 8192, true>(nat_t);
+          fo[i] = *reinterpret_cast<const __attribute__((address_space(3))) bf16x8_t*>(a + kTileBytes + qb * 8192);
         };
         static_for<kA>(rd);
         __builtin_amdgcn_s_setprio(1);
