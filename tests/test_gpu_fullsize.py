@@ -3,7 +3,7 @@ and the kernel entry points of the C ABI on the C2 .. C5 shapes).
 
 C2 (T = 8192) is small enough for the complete fp64 oracle: every output is compared element by
 element.  At the C3, C4 and C5 widths the oracle evaluates sampled outputs one by one from the
-plain definition: rows of y and the tail of dx of the whole C3 layer; 8 x 8 blocks of every GEMM
+plain definition: rows of y and the tail of dx of the whole layer; 8 x 8 blocks of every GEMM
 output (the forward projections, the rotated qkv projection, and the paired input-gradient /
 weight-gradient launch of every backward linear); attention rows and the tail of the attention
 gradients, with and without the rotary backward; rows of the row-wise kernels; the RMSNorm gain
@@ -36,13 +36,14 @@ def test_c2_layer_against_the_complete_oracle(taw):
     U.check_layer(taw, I.CONFIGS["C2"], seed=0)
 
 
-def test_c3_layer_sampled_rows_and_backward_tail(taw):
-    """The whole C3 layer through taw_layer_fwd and taw_layer_bwd: y at sampled token rows (first, last,
-    both sides of tile boundaries) and dx at the last 256 positions, which the oracle obtains from the
-    plain definition as a closed sub-problem (a query's gradient needs its own row of probabilities; keys
-    at u >= t0 are seen by the queries t >= t0 only)."""
+@pytest.mark.parametrize("width", ["C3", "C4", "C5"])
+def test_layer_sampled_rows_and_backward_tail(taw, width):
+    """The whole layer at the widths of C3, C4 and C5 through taw_layer_fwd and taw_layer_bwd: y at sampled token rows
+    (first, last, both sides of tile boundaries) of the last batch element and dx at its last 256 positions, which the
+    oracle obtains from the plain definition as a closed sub-problem (a query's gradient needs its own row of
+    probabilities; keys at u >= t0 are seen by the queries t >= t0 only)."""
     import torch
-    cfg = C3
+    cfg = I.CONFIGS[width]
     w = I.make_weights(cfg, 0)
     x, dy = I.make_activations(cfg, 0)
     L = U.DeviceLayer(taw, cfg)
@@ -51,17 +52,20 @@ def test_c3_layer_sampled_rows_and_backward_tail(taw):
     y = L.fwd(xd)
     dx = L.bwd(xd, dyd)
     torch.cuda.synchronize()
+    b = cfg.B - 1
     w64 = I.weights_to_f64(w, cfg.dtype)
-    x64 = I.to_f64(x, cfg.dtype)[0]
-    rows = np.array([0, 1, 63, 64, 255, 256, 4097, 16383, 16384, 32511, 32767])
+    del w
+    x64 = I.to_f64(x[b], cfg.dtype)
+    S = cfg.S
+    rows = np.array([0, 1, 63, 64, 255, 256, 4097, S // 2 - 1, S // 2, S - 257, S - 1])
     yr = O.layer_fwd_rows(w64, x64, rows, cfg.n_heads, cfg.rope_theta, cfg.rms_eps)
-    e_y = U.tensor_scale_err(f64(y[0, torch.from_numpy(rows).cuda()]), yr)
-    print(f"C3 y rows: {e_y:.2e}", flush=True)
+    e_y = U.tensor_scale_err(f64(y[b, torch.from_numpy(rows).cuda()]), yr)
+    print(f"{width} y rows: {e_y:.2e}", flush=True)
     assert e_y < TOL
-    t0 = cfg.S - 256
-    dxr = O.layer_bwd_tail(w64, x64, I.to_f64(dy, cfg.dtype)[0], t0, cfg.n_heads, cfg.rope_theta, cfg.rms_eps)
-    e_dx = U.tensor_scale_err(f64(dx[0, t0:]), dxr)
-    print(f"C3 dx tail (last 256 positions): {e_dx:.2e}", flush=True)
+    t0 = S - 256
+    dxr = O.layer_bwd_tail(w64, x64, I.to_f64(dy[b], cfg.dtype), t0, cfg.n_heads, cfg.rope_theta, cfg.rms_eps)
+    e_dx = U.tensor_scale_err(f64(dx[b, t0:]), dxr)
+    print(f"{width} dx tail (last 256 positions): {e_dx:.2e}", flush=True)
     assert e_dx < TOL
 
 
