@@ -611,6 +611,22 @@ def run_diag(env):
         out["gemm_by_tiles"].append({"M": M, "N": N, "K": K, "tiles": tiles, "ms": round(t, 4), "TFLOPs": round(tf, 1),
                                      "TFLOPs_per_busy_compute_unit": round(tf / min(tiles, 256), 2)})
         del A, Bm, Cm
+    # the same kernel over K at fixed M, N (8 rounds of 256 tiles): the time per round is a fixed cost per tile (prologue and
+    # epilogue) plus K / 64 main-loop steps; a straight line through the two shortest K gives the fixed cost
+    out["gemm_by_K"] = []
+    M, N = 32768, 4096
+    Cm = torch.empty(M * N, dtype=torch.bfloat16, device="cuda")
+    for K in (1024, 2048, 4096, 8192, 16384):
+        A = torch.empty(M * K, dtype=torch.bfloat16, device="cuda").normal_()
+        Bm = torch.empty(N * K, dtype=torch.bfloat16, device="cuda").normal_(std=0.02)
+        t = env.ev_time(lambda: taw.taw_op_gemm(BF, taw.TAW_GEMM_NT, M, N, K, A, K, Bm, K, Cm, N, BF, 0, None, 0, taw.TAW_IMPL_MFMA, env.compute), 10)
+        rounds = (M // 256) * (N // 256) / 256
+        out["gemm_by_K"].append({"M": M, "N": N, "K": K, "ms": round(t, 4), "TFLOPs": round(2.0 * M * N * K / t / 1e9, 1),
+                                 "us_per_round_of_tiles": round(1e3 * t / rounds, 2)})
+        del A, Bm
+    g = out["gemm_by_K"]
+    per_1024 = g[1]["us_per_round_of_tiles"] - g[0]["us_per_round_of_tiles"]
+    out["gemm_fixed_us_per_tile"] = round(g[0]["us_per_round_of_tiles"] - per_1024, 2)
     return out
 
 
