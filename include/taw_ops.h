@@ -106,9 +106,15 @@ int taw_op_qkv_rope(int32_t dtype, int32_t B, int32_t S, int32_t n_heads, int32_
  *   dx [T, K] = dy W              (storage type dtype)
  *   G  [N, K] (=|+=) dy^T x       (fp32; += when accumulate != 0)
  * On the MFMA path the two products share one grid when T and N are multiples of 32.
+ * scratch: device, fp32, taw_op_linear_bwd_scratch_floats(T, N, K) elements, or NULL.  A narrow layer's weight gradient
+ * has few 256 x 256 tiles, each contracting over all T tokens; with scratch given (and that count not 0) the contraction
+ * is cut into ranges of tokens whose partial products land in scratch and are summed into G in a fixed order by a
+ * second kernel: deterministic, equal to the uncut result up to the order of fp32 additions.  NULL, or a count of 0:
+ * one kernel, no second pass.  Contents are overwritten; the caller clears nothing.
  * A dimension of 0 makes the call a no-op (G is left as it is). */
+size_t taw_op_linear_bwd_scratch_floats(int64_t T, int64_t N, int64_t K);
 int taw_op_linear_bwd(int32_t dtype, int64_t T, int64_t N, int64_t K, const void* dy, const void* W, const void* x,
-                      void* dx, float* G, int32_t accumulate, int32_t impl, void* stream);
+                      void* dx, float* G, int32_t accumulate, float* scratch, int32_t impl, void* stream);
 
 #ifdef __cplusplus
 }

@@ -91,7 +91,8 @@ _SIGS = {
     "taw_op_attn_fwd": (C.c_int, [_i32, _i32, _i32, _i32, _i32, _vp, _vp, _vp, _i32, _vp]),
     "taw_op_attn_bwd": (C.c_int, [_i32, _i32, _i32, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _vp]),
     "taw_op_qkv_rope": (C.c_int, [_i32, _i32, _i32, _i32, _i32, _vp, _vp, _vp, _vp, _i32, _vp]),
-    "taw_op_linear_bwd": (C.c_int, [_i32, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _vp]),
+    "taw_op_linear_bwd_scratch_floats": (C.c_size_t, [_i64, _i64, _i64]),
+    "taw_op_linear_bwd": (C.c_int, [_i32, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _vp, _i32, _vp, _i32, _vp]),
 }
 EXPORTS = tuple(_SIGS)
 
@@ -296,8 +297,12 @@ def taw_op_qkv_rope(dtype, B, S, n_heads, head_dim, xn, w_qkv, qkv, rope_table, 
     _check(load().taw_op_qkv_rope(dtype, B, S, n_heads, head_dim, _p(xn), _p(w_qkv), _p(qkv), _p(rope_table), impl, _stream(stream)))
 
 
-def taw_op_linear_bwd(dtype, T, N, K, dy, W, x, dx, G, accumulate=0, impl=TAW_IMPL_AUTO, stream=None):
-    _check(load().taw_op_linear_bwd(dtype, T, N, K, _p(dy), _p(W), _p(x), _p(dx), _p(G), accumulate, impl, _stream(stream)))
+def taw_op_linear_bwd_scratch_floats(T, N, K):
+    return int(load().taw_op_linear_bwd_scratch_floats(T, N, K))
+
+
+def taw_op_linear_bwd(dtype, T, N, K, dy, W, x, dx, G, accumulate=0, impl=TAW_IMPL_AUTO, stream=None, scratch=None):
+    _check(load().taw_op_linear_bwd(dtype, T, N, K, _p(dy), _p(W), _p(x), _p(dx), _p(G), accumulate, _p(scratch), impl, _stream(stream)))
 
 
 # ----------------------------------------------------------------------------- taw_diag.h (each call waits for its kernel)

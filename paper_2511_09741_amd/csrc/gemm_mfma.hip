@@ -581,16 +581,34 @@ struct GemmArgs {
   int64_t ldr;
   int tiles_m, tiles_n;
   EpiArgs epi;            // fused epilogues only
+  // TN only: the contraction cut into `splits` ranges of k_chunk rows, one workgroup per (range, tile); range s writes its
+  // partial product, dense [M][N] fp32, to part + s * M * N, and a second kernel sums the ranges into C in a fixed order
+  int splits;
+  int64_t k_chunk;
+  float* part;
 };
 
 template <int MODE, bool C_F32>
 __device__ __forceinline__ void gemm_dlds_body(const GemmArgs& ga, int block) {
-  const int64_t M = ga.M, N = ga.N, K = ga.K, lda = ga.lda, ldb = ga.ldb, ldc = ga.ldc, ldr = ga.ldr;
+  const int64_t M = ga.M, N = ga.N, lda = ga.lda, ldb = ga.ldb, ldr = ga.ldr;
+  int64_t K = ga.K, ldc = ga.ldc;
   const bf16_t* __restrict__ A = ga.A;
   const bf16_t* __restrict__ B = ga.B;
   void* __restrict__ Cv = ga.C;
   const void* __restrict__ Rv = ga.R;
-  const int accumulate = ga.accumulate, tiles_m = ga.tiles_m, tiles_n = ga.tiles_n;
+  int accumulate = ga.accumulate;
+  const int tiles_m = ga.tiles_m, tiles_n = ga.tiles_n;
+  if (MODE == GEMM_TN && C_F32 && ga.splits > 1) {      // workgroup-uniform: this workgroup's range of the contraction
+    const int ntl = tiles_m * tiles_n, sp = block / ntl;
+    block -= sp * ntl;
+    const int64_t k0 = (int64_t)sp * ga.k_chunk;
+    A += k0 * lda;
+    B += k0 * ldb;
+    K = K - k0 < ga.k_chunk ? K - k0 : ga.k_chunk;
+    Cv = ga.part + (int64_t)sp * M * N;
+    ldc = N;
+    accumulate = 0;
+  }
   constexpr bool A_KC = (MODE != GEMM_TN);
   constexpr bool B_KC = (MODE == GEMM_NT);
   extern __shared__ __attribute__((aligned(16))) unsigned char lds2[];
@@ -915,6 +933,9 @@ inline GemmArgs make_args(int64_t M, int64_t N, int64_t K, const void* A, int64_
   g.tiles_m = (int)((M + BM - 1) / BM);
   g.tiles_n = (int)((N + BN - 1) / BN);
   g.epi = EpiArgs{nullptr, 1, 0};
+  g.splits = 1;
+  g.k_chunk = K;
+  g.part = nullptr;
   return g;
 }
 
@@ -930,7 +951,7 @@ int launch_pipe(const GemmArgs& g, hipStream_t st) {
 template <int MODE0, bool F32_0, bool K64_0, int MODE1, bool F32_1, bool K64_1>
 int launch_dual(const GemmArgs& g0, const GemmArgs& g1, hipStream_t st) {
   TAW_SET_LDS_LIMIT_ONCE((gemm_dual_kernel<MODE0, F32_0, K64_0, MODE1, F32_1, K64_1>), kLds2);
-  const int n0 = g0.tiles_m * g0.tiles_n, n1 = g1.tiles_m * g1.tiles_n;
+  const int n0 = g0.tiles_m * g0.tiles_n * g0.splits, n1 = g1.tiles_m * g1.tiles_n;
   hipLaunchKernelGGL((gemm_dual_kernel<MODE0, F32_0, K64_0, MODE1, F32_1, K64_1>), dim3((unsigned)(n0 + n1)), dim3(kThreads), kLds2, st, g0, g1, n0);
   return (int)hipGetLastError();
 }
@@ -993,15 +1014,56 @@ int launch_gemm_mfma(int mode, int64_t M, int64_t N, int64_t K, const void* A, i
   }
 }
 
+// C[M][N] (row stride ldc) = (accumulate ? C : 0) + part[0] + part[1] + ... + part[splits - 1], in that order; N % 4 == 0
+__global__ void __launch_bounds__(256) splitk_reduce_kernel(float* __restrict__ C, int64_t ldc, const float* __restrict__ part, int splits,
+                                                            int64_t M, int64_t N, int accumulate) {
+  const int64_t n4 = N / 4, total = M * n4;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
+    const int64_t r = i / n4, c4 = i - r * n4;
+    float* cp = C + r * ldc + c4 * 4;
+    f32x4_t v = accumulate ? *reinterpret_cast<const f32x4_t*>(cp) : f32x4_t{0.f, 0.f, 0.f, 0.f};
+    const float* pp = part + r * N + c4 * 4;
+    for (int sidx = 0; sidx < splits; ++sidx) v += __builtin_nontemporal_load(reinterpret_cast<const f32x4_t*>(pp + (int64_t)sidx * M * N));
+    *reinterpret_cast<f32x4_t*>(cp) = v;
+  }
+}
+
+// Into how many ranges the weight gradient of the linear y[T, N] = x[T, K] W^T is cut (1 = not at all), and the rows per
+// range.  Its tiles contract over all T tokens: with few of them (narrow layers) a tile runs long after everything else
+// in the grid is done, most compute units idle.  The ranges are sized so that one takes at most about half of what a
+// compute unit's fair share of the whole grid (both GEMMs) takes; never shorter than 512 rows, never more than 32 ranges.
+int gemm_dual_splits(int64_t T, int64_t N, int64_t K, int64_t* k_chunk) {
+  const int64_t tn_tiles = ((N + BM - 1) / BM) * ((K + BN - 1) / BN), nn_tiles = ((T + BM - 1) / BM) * ((K + BN - 1) / BN);
+  const double fair = ((double)tn_tiles * (double)T + (double)nn_tiles * (double)N) / 256.0;     // contraction rows per compute unit
+  int64_t sp = fair > 0 ? (int64_t)(2.0 * (double)T / fair + 0.999) : 1;
+  if (sp > 32) sp = 32;
+  if (sp > T / 512) sp = T / 512;
+  if (sp < 2) { *k_chunk = T; return 1; }
+  int64_t chunk = ((T + sp - 1) / sp + 63) / 64 * 64;
+  sp = (T + chunk - 1) / chunk;
+  *k_chunk = chunk;
+  return (int)sp;
+}
+
 bool gemm_mfma_dual_supported(int64_t K_tn, int64_t K_nn) { return K_tn >= v2::BK2 && K_tn % v2::BK2 == 0 && K_nn >= v2::BK2 && K_nn % v2::BK2 == 0; }
 
 int launch_gemm_mfma_dual(int64_t M0, int64_t N0, int64_t K0, const void* A0, int64_t lda0, const void* B0, int64_t ldb0, float* C0,
                           int64_t ldc0, int accumulate0, int64_t M1, int64_t N1, int64_t K1, const void* A1, int64_t lda1,
-                          const void* B1, int64_t ldb1, void* C1, int64_t ldc1, hipStream_t st) {
-  const v2::GemmArgs g0 = v2::make_args(M0, N0, K0, A0, lda0, B0, ldb0, C0, ldc0, accumulate0, nullptr, 0);
+                          const void* B1, int64_t ldb1, void* C1, int64_t ldc1, float* part, int splits, int64_t k_chunk, hipStream_t st) {
+  v2::GemmArgs g0 = v2::make_args(M0, N0, K0, A0, lda0, B0, ldb0, C0, ldc0, accumulate0, nullptr, 0);
   const v2::GemmArgs g1 = v2::make_args(M1, N1, K1, A1, lda1, B1, ldb1, C1, ldc1, 0, nullptr, 0);
-  if (K1 % v2::BK64 == 0) return v2::launch_dual<GEMM_TN, true, false, GEMM_NN, false, true>(g0, g1, st);
-  return v2::launch_dual<GEMM_TN, true, false, GEMM_NN, false, false>(g0, g1, st);
+  if (part && splits > 1) {
+    g0.splits = splits;
+    g0.k_chunk = k_chunk;
+    g0.part = part;
+  }
+  const int rc = K1 % v2::BK64 == 0 ? v2::launch_dual<GEMM_TN, true, false, GEMM_NN, false, true>(g0, g1, st)
+                                    : v2::launch_dual<GEMM_TN, true, false, GEMM_NN, false, false>(g0, g1, st);
+  if (rc || g0.splits == 1) return rc;
+  const int64_t total = M0 * (N0 / 4);
+  const unsigned blocks = (unsigned)((total + 255) / 256 < 2048 ? (total + 255) / 256 : 2048);
+  hipLaunchKernelGGL(splitk_reduce_kernel, dim3(blocks), dim3(256), 0, st, C0, ldc0, part, g0.splits, M0, N0, accumulate0);
+  return (int)hipGetLastError();
 }
 
 bool gemm_mfma_rope_supported(int64_t M, int64_t N, int64_t K, int64_t rot_cols, int S) {

@@ -1,6 +1,7 @@
 // C-ABI front end: argument validation, weight-chunk layout, ctx/workspace partition and the
 // kernel sequence of the layer's forward and backward pass.  Host code only; every arithmetic
 // step is a kernel from the other files of this directory.
+#include <algorithm>
 #include <hip/hip_runtime.h>
 #include <cstdio>
 #include <cstring>
@@ -115,8 +116,16 @@ struct Ctx {       // saved by the forward for the backward
   void *xn, *qkv, *o, *h, *hn, *gu, *a; float *lse, *r1, *r2; size_t bytes;
 };
 struct Work {      // scratch of the backward (the forward needs none of it)
-  void *da, *dgu, *dhn, *dh, *dO, *dqkv, *dxn; float *D, *partials; size_t bytes;
+  void *da, *dgu, *dhn, *dh, *dO, *dqkv, *dxn; float *D, *partials, *splitk; size_t bytes;
 };
+
+// fp32 elements of partial weight gradients the backward of the linear y[T,N] = x[T,K] W^T needs (0: its weight gradient is not cut)
+static size_t linear_bwd_scratch_floats(int64_t T, int64_t N, int64_t K) {
+  if (T <= 0 || N <= 0 || K <= 0) return 0;
+  int64_t chunk;
+  const int sp = gemm_dual_splits(T, N, K, &chunk);
+  return sp > 1 ? (size_t)sp * (size_t)N * (size_t)K : 0;
+}
 
 static Ctx carve_ctx(const taw_layer_desc* d, void* base) {
   const size_t e = dt_size(d->dtype), T = (size_t)d->B * d->S, H = d->H, I = d->I;
@@ -135,6 +144,11 @@ static Work carve_work(const taw_layer_desc* d, void* base) {
   w.dO = c.take(T * H * e); w.dqkv = c.take(T * 3 * H * e); w.dxn = c.take(T * H * e);
   w.D = (float*)c.take(attn_bwd_mfma_scratch_floats(d->B, d->S, d->n_heads, (d->flags & TAW_ATTN_BWD_FUSED) != 0) * 4);   // covers the generic kernel's B*nh*S too
   w.partials = (float*)c.take((size_t)rmsnorm_bwd_partial_rows() * H * 4);
+  size_t sk = linear_bwd_scratch_floats((int64_t)T, (int64_t)H, (int64_t)I);                  // down
+  sk = std::max(sk, linear_bwd_scratch_floats((int64_t)T, (int64_t)(2 * I), (int64_t)H));     // gate, up
+  sk = std::max(sk, linear_bwd_scratch_floats((int64_t)T, (int64_t)H, (int64_t)H));           // output projection
+  sk = std::max(sk, linear_bwd_scratch_floats((int64_t)T, (int64_t)(3 * H), (int64_t)H));     // q, k, v
+  w.splitk = (float*)c.take(sk * 4);
   w.bytes = c.off;
   return w;
 }
@@ -164,12 +178,17 @@ static int gemm(const Plan& p, int dtype, int mode, int64_t M, int64_t N, int64_
 }
 
 // Backward of a linear y[T,N] = x[T,K] W[N,K]^T given dy: dx[T,K] = dy W (NN) and G[N,K] (+)= dy^T x (TN).
-// The two are independent; on the MFMA path they share one grid.
+// The two are independent; on the MFMA path they share one grid, and where the weight gradient has too few tiles to
+// fill its share of the chip it is cut along T into partial products in `part` (linear_bwd_scratch_floats elements;
+// nullptr: never cut), summed in a fixed order by a second kernel: the result does not depend on scheduling.
 static int linear_bwd(const Plan& p, int dtype, int64_t T, int64_t N, int64_t K, const void* dy, const void* W, const void* x,
-                      void* dx, float* G, int accumulate, hipStream_t st) {
+                      void* dx, float* G, int accumulate, float* part, hipStream_t st) {
   if (p.mfma_gemm && gemm_mfma_supported(dtype, GEMM_NN, T, K, N, N, K, K, dtype, 0) &&
-      gemm_mfma_supported(dtype, GEMM_TN, N, K, T, N, K, K, DT_F32, 0) && gemm_mfma_dual_supported(T, N))
-    return launch_gemm_mfma_dual(N, K, T, dy, N, x, K, G, K, accumulate, T, K, N, dy, N, W, K, dx, K, st);
+      gemm_mfma_supported(dtype, GEMM_TN, N, K, T, N, K, K, DT_F32, 0) && gemm_mfma_dual_supported(T, N)) {
+    int64_t chunk = T;
+    const int sp = part ? gemm_dual_splits(T, N, K, &chunk) : 1;
+    return launch_gemm_mfma_dual(N, K, T, dy, N, x, K, G, K, accumulate, T, K, N, dy, N, W, K, dx, K, part, sp, chunk, st);
+  }
   int rc = gemm(p, dtype, GEMM_NN, T, K, N, dy, N, W, K, dx, K, dtype, 0, nullptr, 0, st);
   if (rc) return rc;
   return gemm(p, dtype, GEMM_TN, N, K, T, dy, N, x, K, G, K, DT_F32, accumulate, nullptr, 0, st);
@@ -273,15 +292,15 @@ extern "C" int taw_layer_bwd(const taw_layer_desc* desc, const void* W_chunk, co
   }
 
   // y = h + a Wd^T :  da = dy Wd ;  G.Wd (+)= dy^T a
-  TAW_LAUNCH(linear_bwd(p, dt, T, H, I, dy, at(W_chunk, L.w_down, dt), c.a, w.da, G_shard + L.w_down, acc, st), "gemm da, G.w_down");
+  TAW_LAUNCH(linear_bwd(p, dt, T, H, I, dy, at(W_chunk, L.w_down, dt), c.a, w.da, G_shard + L.w_down, acc, w.splitk, st), "gemm da, G.w_down");
   // a = silu(g) u
   TAW_LAUNCH(launch_swiglu_bwd(dt, T, (int)I, w.da, c.gu, w.dgu, st), "swiglu_bwd");
   // gu = hn Wgu^T :  dhn = dgu Wgu ;  G.Wgu (+)= dgu^T hn
-  TAW_LAUNCH(linear_bwd(p, dt, T, 2 * I, H, w.dgu, at(W_chunk, L.w_gate_up, dt), c.hn, w.dhn, G_shard + L.w_gate_up, acc, st), "gemm dhn, G.w_gate_up");
+  TAW_LAUNCH(linear_bwd(p, dt, T, 2 * I, H, w.dgu, at(W_chunk, L.w_gate_up, dt), c.hn, w.dhn, G_shard + L.w_gate_up, acc, w.splitk, st), "gemm dhn, G.w_gate_up");
   // hn = rmsnorm(h) :  dh = dy + rmsnorm_bwd(dhn) ;  G.gamma_mlp
   TAW_LAUNCH(launch_rmsnorm_bwd(dt, T, (int)H, w.dhn, c.h, c.r2, at(W_chunk, L.gamma_mlp, dt), dy, w.dh, G_shard + L.gamma_mlp, acc, w.partials, st), "rmsnorm_bwd(mlp)");
   // h = x + o Wo^T :  do = dh Wo ;  G.Wo (+)= dh^T o
-  TAW_LAUNCH(linear_bwd(p, dt, T, H, H, w.dh, at(W_chunk, L.w_o, dt), c.o, w.dO, G_shard + L.w_o, acc, st), "gemm do, G.w_o");
+  TAW_LAUNCH(linear_bwd(p, dt, T, H, H, w.dh, at(W_chunk, L.w_o, dt), c.o, w.dO, G_shard + L.w_o, acc, w.splitk, st), "gemm do, G.w_o");
   // attention backward
   // attention backward, then the rotary backward on dq, dk (the MFMA kernels apply it to their accumulators before storing)
   if (p.mfma_attn) {
@@ -293,7 +312,7 @@ extern "C" int taw_layer_bwd(const taw_layer_desc* desc, const void* W_chunk, co
     TAW_LAUNCH(launch_rope(dt, desc->B, desc->S, (int)(2 * H), desc->head_dim, w.dqkv, 3 * H, rope_table, 1, st), "rope bwd");
   }
   // qkv = xn Wqkv^T :  dxn = dqkv Wqkv ;  G.Wqkv (+)= dqkv^T xn
-  TAW_LAUNCH(linear_bwd(p, dt, T, 3 * H, H, w.dqkv, at(W_chunk, L.w_qkv, dt), c.xn, w.dxn, G_shard + L.w_qkv, acc, st), "gemm dxn, G.w_qkv");
+  TAW_LAUNCH(linear_bwd(p, dt, T, 3 * H, H, w.dqkv, at(W_chunk, L.w_qkv, dt), c.xn, w.dxn, G_shard + L.w_qkv, acc, w.splitk, st), "gemm dxn, G.w_qkv");
   // xn = rmsnorm(x) :  dx = dh + rmsnorm_bwd(dxn) ;  G.gamma_attn
   TAW_LAUNCH(launch_rmsnorm_bwd(dt, T, (int)H, w.dxn, x, c.r1, at(W_chunk, L.gamma_attn, dt), w.dh, dx, G_shard + L.gamma_attn, acc, w.partials, st), "rmsnorm_bwd(attn)");
   return TAW_OK;
@@ -576,8 +595,10 @@ extern "C" int taw_op_qkv_rope(int32_t dtype, int32_t B, int32_t S, int32_t n_he
   return TAW_OK;
 }
 
+extern "C" size_t taw_op_linear_bwd_scratch_floats(int64_t T, int64_t N, int64_t K) { return linear_bwd_scratch_floats(T, N, K); }
+
 extern "C" int taw_op_linear_bwd(int32_t dtype, int64_t T, int64_t N, int64_t K, const void* dy, const void* W, const void* x, void* dx,
-                                 float* G, int32_t accumulate, int32_t impl, void* stream) {
+                                 float* G, int32_t accumulate, float* scratch, int32_t impl, void* stream) {
   int rc = check_dtype(dtype);
   if (rc) return rc;
   if (T < 0 || N < 0 || K < 0) return fail(TAW_ERR_SHAPE, "negative dimension");
@@ -592,6 +613,7 @@ extern "C" int taw_op_linear_bwd(int32_t dtype, int64_t T, int64_t N, int64_t K,
   Plan p;
   p.mfma_gemm = can && impl != TAW_IMPL_GENERIC;
   p.mfma_attn = false;
-  TAW_LAUNCH(linear_bwd(p, dtype, T, N, K, dy, W, x, dx, G, accumulate ? 1 : 0, st), "linear backward");
+  if (scratch) TAW_REQUIRE_ALIGNED(scratch);
+  TAW_LAUNCH(linear_bwd(p, dtype, T, N, K, dy, W, x, dx, G, accumulate ? 1 : 0, scratch, st), "linear backward");
   return TAW_OK;
 }

@@ -107,9 +107,14 @@ int launch_gemm_mfma(int mode, int64_t M, int64_t N, int64_t K, const void* A, i
 // A weight gradient C0[M0,N0] (fp32, TN form, optionally accumulated) and an input gradient C1[M1,N1] (bf16, NN form) in one
 // grid: the pair every linear of the backward has.  Needs both K % 32 == 0 on top of gemm_mfma_supported for each.
 bool gemm_mfma_dual_supported(int64_t K_tn, int64_t K_nn);
+// part / splits / k_chunk: the weight gradient cut into `splits` ranges of k_chunk contraction rows (gemm_dual_splits), their
+// partial products in part[splits][M0][N0] fp32, summed into C0 by a second kernel in a fixed order; splits <= 1 or part ==
+// nullptr: not cut
 int launch_gemm_mfma_dual(int64_t M0, int64_t N0, int64_t K0, const void* A0, int64_t lda0, const void* B0, int64_t ldb0, float* C0,
                           int64_t ldc0, int accumulate0, int64_t M1, int64_t N1, int64_t K1, const void* A1, int64_t lda1,
-                          const void* B1, int64_t ldb1, void* C1, int64_t ldc1, hipStream_t st);
+                          const void* B1, int64_t ldb1, void* C1, int64_t ldc1, float* part, int splits, int64_t k_chunk, hipStream_t st);
+// ranges (and rows per range) for the weight gradient of the linear y[T, N] = x[T, K] W^T; 1 = not cut
+int gemm_dual_splits(int64_t T, int64_t N, int64_t K, int64_t* k_chunk);
 // C[M,N] = A[M,K] B[N,K]^T (bf16) with the rotary embedding applied in the epilogue to the columns below rot_cols (heads of
 // 128, adjacent pairs, row r at position r % S; table [S, 64, 2] fp32).  Needs M % 256 == 0, N % 256 == 0, K % 64 == 0,
 // rot_cols % 256 == 0, S >= 32.

@@ -31,7 +31,7 @@ def declared_functions():
 
 def test_every_declared_symbol_is_exported(lib):
     names = declared_functions()
-    assert len(names) == 34
+    assert len(names) == 35
     for n in names:
         assert hasattr(lib, n), f"{n} declared in include/ but not exported"
     assert set(names) == set(taw.EXPORTS)
@@ -261,3 +261,20 @@ def test_missing_library_fails_loudly(monkeypatch, tmp_path):
     monkeypatch.setattr(taw, "LIB_PATH", str(tmp_path / "nope.so"))
     with pytest.raises(ImportError):
         taw.load()
+
+
+def test_linear_bwd_scratch_rule(lib):
+    """The weight gradient is cut only where it has too few tiles for its share of the chip: never at the 4096- and
+    5120-wide layers, at most 32 ranges of at least 512 tokens elsewhere, nothing for empty or tiny problems."""
+    f = taw.taw_op_linear_bwd_scratch_floats
+    for T in (8192, 32768, 65536):
+        for H, Iw in ((4096, 11008), (5120, 13824)):
+            for N, K in ((H, Iw), (2 * Iw, H), (H, H), (3 * H, H)):
+                assert f(T, N, K) == 0
+    for T, N, K in ((65536, 1024, 1024), (65536, 1024, 2816), (65536, 3072, 1024), (65536, 2048, 2048), (2080, 256, 256), (1 << 20, 8, 8)):
+        n = f(T, N, K)
+        assert n > 0 and n % (N * K) == 0
+        splits = n // (N * K)
+        assert 2 <= splits <= 32 and T // splits >= 512 - 64
+    for T, N, K in ((0, 8, 8), (8, 0, 8), (-1, 8, 8), (256, 256, 256), (1023, 8, 8)):
+        assert f(T, N, K) == 0

@@ -197,6 +197,46 @@ def test_backward_linears_paired_launch_sampled_blocks(taw, width):
         del dyy, W, x, G, G0, dx
 
 
+@pytest.mark.parametrize("T,N,K", [(2080, 256, 256), (4096, 264, 520), (65536, 1024, 1024), (65536, 1024, 2816), (65536, 2048, 2048), (65536, 6144, 2048)],
+                         ids=lambda v: str(v))
+def test_backward_linear_weight_gradient_cut_along_tokens(taw, T, N, K):
+    """Narrow linears (the 1024- and 2048-wide models of the paper's throughput table, and two small ragged shapes): the
+    weight gradient computed in ranges of tokens and summed by a second kernel.  Sampled blocks of G and dx against fp64
+    dot products, with and without accumulation; the same call twice gives the same bits; and the uncut launch (no
+    scratch) agrees to fp32 summation order."""
+    import torch
+    n_scr = taw.taw_op_linear_bwd_scratch_floats(T, N, K)
+    assert n_scr > 0 and n_scr % (N * K) == 0 and 2 <= n_scr // (N * K) <= 32
+    scratch = torch.full((n_scr,), float("nan"), dtype=torch.float32, device="cuda")     # stale contents must not matter
+    dyy = I.device_normal((T, N), seed=27, std=1.0)
+    W = I.device_normal((N, K), seed=28, std=0.02)
+    x = I.device_normal((T, K), seed=29, std=1.0)
+    G0 = I.device_normal((N, K), seed=30, std=1.0, dtype=torch.float32)
+    dx = torch.empty((T, K), dtype=torch.bfloat16, device="cuda")
+    rng = np.random.default_rng(T + N + K)
+    for accumulate in (1, 0):
+        G = G0.clone()
+        taw.taw_op_linear_bwd(BF, T, N, K, dyy, W, x, dx, G, accumulate, taw.TAW_IMPL_MFMA, scratch=scratch)
+        G_again, dx_again = G0.clone(), torch.empty_like(dx)
+        taw.taw_op_linear_bwd(BF, T, N, K, dyy, W, x, dx_again, G_again, accumulate, taw.TAW_IMPL_MFMA, scratch=scratch)
+        G_uncut = G0.clone()
+        taw.taw_op_linear_bwd(BF, T, N, K, dyy, W, x, dx_again, G_uncut, accumulate, taw.TAW_IMPL_MFMA)
+        torch.cuda.synchronize()
+        assert torch.equal(G, G_again) and torch.equal(dx, dx_again)
+        scale = float(G_uncut.abs().max())
+        assert float((G - G_uncut).abs().max()) < 2e-5 * scale
+        p_dx, p_g = [], []
+        for rows, cols in _blocks(rng, T, K):
+            ri, ci = _idx(rows), _idx(cols)
+            p_dx.append((f64(dx[ri][:, ci]), f64(dyy[ri, :]) @ f64(W[:, ci])))
+        for rows, cols in _blocks(rng, N, K):
+            ri, ci = _idx(rows), _idx(cols)
+            p_g.append((f64(G[ri][:, ci]), f64(dyy[:, ri]).T @ f64(x[:, ci]) + accumulate * f64(G0[ri][:, ci])))
+        e_dx, e_g = _block_err(p_dx), _block_err(p_g)
+        print(f"linear backward, cut into {n_scr // (N * K)}: T={T} N={N} K={K} accumulate={accumulate}: dx={e_dx:.2e} G={e_g:.2e}", flush=True)
+        assert e_dx < TOL and e_g < 1e-4
+
+
 @pytest.mark.parametrize("width,form", [(w, 2) for w in WIDTHS] + [("C3", 3), ("C4", 3)], ids=[w + "-split" for w in WIDTHS] + ["C3-fused", "C4-fused"])
 def test_attention_sampled(taw, width, form):
     """Attention at the layer's shape (all heads, all batch elements in one launch): o and lse at
