@@ -104,8 +104,12 @@ def test_bf16_layer_on_mfma_kernels(taw, B, S, nh, I_, sigma):
 def test_bf16_layer_at_the_widths_of_the_papers_throughput_table(taw, H, nh, B, S):
     """The narrower models of the paper's throughput table (Experiments, Throughput and Memory Usage: H = 1024 and 2048,
     heads of 128, I = 8H/3 rounded up to 256, micro-batches of several sequences): whole layer against the oracle, every
-    element, at a reduced sequence length."""
+    element, at a reduced sequence length.  The first case has 2048 tokens: all four of its weight gradients are computed in
+    3 - 4 ranges of tokens and summed by the second kernel, as at the table's own sizes."""
     cfg = I.LayerConfig(f"table-{H}", I.BF16, B, S, H, nh, 128, (8 * H // 3 + 255) // 256 * 256)
+    T = B * S
+    cut = [taw.taw_op_linear_bwd_scratch_floats(T, N, K) > 0 for N, K in ((H, cfg.I), (2 * cfg.I, H), (H, H), (3 * H, H))]
+    assert all(cut) == (H == 1024)
     U.check_layer(taw, cfg, seed=H + S)
 
 
