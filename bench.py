@@ -74,7 +74,7 @@ PAPER_TABLE_TAWPIPE = {(1024, 4096): 13629.2, (1024, 8192): 11738.2, (1024, 1638
 PAPER_SETUP = "24 x A800, NVLink + 10GbE, fp16, activation checkpointing, 48 layers (context, not the target)"
 # matrix products the attention backward executes per (query tile, key tile) pair; 4 are credited (dV, dP, dK, dQ) and the
 # score recomputation is a fifth that every tiled backward needs
-ATTN_BWD_PRODUCTS_EXECUTED = 7
+ATTN_BWD_PRODUCTS_EXECUTED = 5
 
 
 def model_flops(cfg):
@@ -352,11 +352,13 @@ def run_layer_workload(env, cfg, steps, warmup, kernel_leg=True, recompute_leg=T
         lse = torch.empty(cfg.B * cfg.n_heads * cfg.S, dtype=torch.float32, device="cuda")
         scr = torch.empty(taw.taw_op_attn_bwd_scratch_floats(cfg.B, cfg.S, cfg.n_heads), dtype=torch.float32, device="cuda")
         tf = ev_time(lambda: taw.taw_op_attn_fwd(BF, cfg.B, cfg.S, cfg.n_heads, cfg.head_dim, qkv, o, lse, taw.TAW_IMPL_MFMA, compute), 3)
-        tb = ev_time(lambda: taw.taw_op_attn_bwd(BF, cfg.B, cfg.S, cfg.n_heads, cfg.head_dim, qkv, o, dO, lse, dqkv, scr, rope, taw.TAW_IMPL_MFMA, compute), 3)
-        # the two other forms of the backward (one kernel, 5 products: dQ partial sums in private slots / fp32 atomics), for the record
+        tb = ev_time(lambda: taw.taw_op_attn_bwd(BF, cfg.B, cfg.S, cfg.n_heads, cfg.head_dim, qkv, o, dO, lse, dqkv, scr, rope, taw.TAW_IMPL_MFMA_STORED, compute), 3)
+        # the other forms of the backward, for the record
         scr_all = scr
-        forms = {"split (default: dK/dV kernel + dQ kernel, 7 products)": round(tb, 4)}
-        for fname, impl in (("fused, dQ slots (5 products, no atomics)", taw.TAW_IMPL_MFMA_FUSED), ("fused, fp32 atomics (5 products)", taw.TAW_IMPL_MFMA_ATOMIC)):
+        forms = {"two kernels, dS stored by the dK/dV kernel and read back by the dQ kernel (default; 5 products)": round(tb, 4)}
+        for fname, impl in (("two kernels, the dQ kernel recomputes the scores (TAW_ATTN_BWD_RECOMPUTE; 7 products)", taw.TAW_IMPL_MFMA),
+                            ("fused, dQ slots (TAW_ATTN_BWD_FUSED; 5 products, no atomics)", taw.TAW_IMPL_MFMA_FUSED),
+                            ("fused, fp32 atomics (5 products)", taw.TAW_IMPL_MFMA_ATOMIC)):
             tt_ = ev_time(lambda: taw.taw_op_attn_bwd(BF, cfg.B, cfg.S, cfg.n_heads, cfg.head_dim, qkv, o, dO, lse, dqkv, scr_all, rope, impl, compute), 2)
             forms[fname] = round(tt_, 4)
         kernels["attn_bwd_forms_ms"] = forms
@@ -374,6 +376,7 @@ def run_layer_workload(env, cfg, steps, warmup, kernel_leg=True, recompute_leg=T
             "avg_launch_ms": round(tb, 4), "flops_per_launch": 4 * prod, "traffic": tr_b[0],
             "traffic_source": (tr_b[1] + " (precomputed by separate counter runs of this file)") if tr_b[1] else None,
             "algorithmic_bytes_per_launch": 2.0 * T * H * (3 + 1 + 1 + 3) + 4.0 * cfg.B * cfg.n_heads * cfg.S,
+            "ds_handover_bytes_per_launch": 2.0 * (2.0 * cfg.B * cfg.n_heads * (((cfg.S + 255) // 256) * ((cfg.S + 255) // 256 + 1) // 2) * 65536),
             "share_of_step": round(tb / st["mean"], 3)}
         rooflines["attn_fwd"] = {
             "kernel": "attn_fwd_kernel", "bound": "mfma", "achieved": round(2 * prod / tf / 1e9, 1), "peak": PEAK_BF16_TFLOPS,

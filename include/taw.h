@@ -60,9 +60,13 @@ typedef enum { TAW_F32 = 0, TAW_BF16 = 1 } taw_dtype;
                              layer's intermediates from x inside the workspace, which is larger by
                              what ctx would have held.  Same results, about 4/3 of the arithmetic. */
 
-#define TAW_ATTN_BWD_FUSED 4u /* taw_layer_bwd runs the attention backward as one kernel that forms the scores once and
-                                 keeps dQ partial sums in private fp32 slots (the workspace grows by those slots), instead of
-                                 the default pair of kernels (dK/dV, then dQ) that each recompute the scores */
+/* Forms of the attention backward on the matrix-core path.  Default: a dK/dV kernel that forms the scores once and also
+   writes dS (bf16) to the workspace, and a dQ kernel that reads it back: five matrix products per tile pair, no atomics,
+   reproducible; the workspace holds about S*S bytes per (batch, head) for it (35 GB at S = 32768 with 32 heads). */
+#define TAW_ATTN_BWD_FUSED 4u /* one kernel that forms the scores once and keeps dQ partial sums in private fp32 slots
+                                 (the workspace holds those slots instead of dS) */
+#define TAW_ATTN_BWD_RECOMPUTE 8u /* the pair of kernels with a dQ kernel that recomputes the scores (seven products):
+                                     needs neither dS nor slots in the workspace; about 12 % slower at S = 32768 */
 
 /* One decoder layer and the micro-batch it is applied to (B, S, H as in the paper's Table 1). */
 typedef struct {
@@ -75,7 +79,7 @@ typedef struct {
   int32_t I;          /* SwiGLU intermediate width */
   float rope_theta;   /* rotary base, 10000 for LLaMA-2 */
   float rms_eps;      /* added to the mean of squares inside the square root */
-  uint32_t flags;     /* TAW_ACCUMULATE | TAW_RECOMPUTE | TAW_ATTN_BWD_FUSED */
+  uint32_t flags;     /* TAW_ACCUMULATE | TAW_RECOMPUTE | TAW_ATTN_BWD_FUSED | TAW_ATTN_BWD_RECOMPUTE */
 } taw_layer_desc;
 
 /* Element offsets of the sub-tensors inside the flat weight chunk W_j (the unit that is moved

@@ -26,7 +26,8 @@ enum { TAW_IMPL_AUTO = 0, TAW_IMPL_GENERIC = 1, TAW_IMPL_MFMA = 2,
           and a dQ kernel that each recompute the scores: 7 matrix products per tile pair), which is the fastest on
           this part; the fused kernel forms the scores once (5 products) and pays for it in dQ traffic. */
        TAW_IMPL_MFMA_FUSED = 3,   /* dQ partial sums in private fp32 slots, one per worker, summed by a last pass: no atomics, reproducible */
-       TAW_IMPL_MFMA_ATOMIC = 4   /* dQ added with fp32 atomics into one buffer (not bit-reproducible) */ };
+       TAW_IMPL_MFMA_ATOMIC = 4,  /* dQ added with fp32 atomics into one buffer (not bit-reproducible) */
+       TAW_IMPL_MFMA_STORED = 5   /* the dK/dV kernel also writes dS (bf16) to the scratch and the dQ kernel reads it back: 5 products, no atomics, reproducible */ };
 enum { TAW_GEMM_NT = 0, TAW_GEMM_NN = 1, TAW_GEMM_TN = 2 };
 
 /* The three products of a linear layer y = x W^T (W is [out, in]):

@@ -16,7 +16,8 @@ TAW_F32, TAW_BF16 = 0, 1
 TAW_ACCUMULATE = 1
 TAW_RECOMPUTE = 2
 TAW_ATTN_BWD_FUSED = 4
-TAW_IMPL_AUTO, TAW_IMPL_GENERIC, TAW_IMPL_MFMA, TAW_IMPL_MFMA_FUSED, TAW_IMPL_MFMA_ATOMIC = 0, 1, 2, 3, 4
+TAW_ATTN_BWD_RECOMPUTE = 8
+TAW_IMPL_AUTO, TAW_IMPL_GENERIC, TAW_IMPL_MFMA, TAW_IMPL_MFMA_FUSED, TAW_IMPL_MFMA_ATOMIC, TAW_IMPL_MFMA_STORED = 0, 1, 2, 3, 4, 5
 TAW_GEMM_NT, TAW_GEMM_NN, TAW_GEMM_TN = 0, 1, 2
 TAW_OK = 0
 TAW_ERR_NULL, TAW_ERR_SHAPE, TAW_ERR_DTYPE, TAW_ERR_ALIGN, TAW_ERR_WORKSPACE, TAW_ERR_UNSUPPORTED, TAW_ERR_HIP = -1, -2, -3, -4, -5, -6, -7

@@ -167,6 +167,11 @@ template <int N> __device__ __forceinline__ void wait_vmcnt() {
 __device__ __forceinline__ void lds_dma16(uint64_t base, unsigned off, unsigned lds_addr) {
   asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(off), "s"(base), "s"(lds_addr));
 }
+// the same with the non-temporal hint: for data read exactly once (it is not worth a place in the caches that the
+// re-read K / V / Q / dO tiles live in)
+__device__ __forceinline__ void lds_dma16_nt(uint64_t base, unsigned off, unsigned lds_addr) {
+  asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1 nt" ::"v"(off), "s"(base), "s"(lds_addr));
+}
 // 4 bytes per lane, same addressing (LDS destination lds_addr + 4 * lane)
 __device__ __forceinline__ void lds_dma4(uint64_t base, unsigned off, unsigned lds_addr) {
   asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dword %0, %1" ::"v"(off), "s"(base), "s"(lds_addr));
@@ -464,10 +469,11 @@ attn_fwd_kernel(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ o, float* _
 // ---- shared epilogue: a wavefront's transposed accumulators X^T[128 d][32 rows] (lane = row,
 // registers = d) -> [32][136] bf16 staging in LDS -> coalesced 16-byte stores of rows of `out`
 // (row stride ld_out elements).  Rows at or beyond `limit` are dropped.
+// lrow: which of the 32 rows this lane's accumulators belong to (lane & 31 unless the producer permuted them)
 __device__ __forceinline__ void store_rows_T(const f32x16_t (&acc)[4], float mul, bf16_t* stage, bf16_t* out,
-                                             int64_t ld_out, int row0, int limit, int lane) {
+                                             int64_t ld_out, int row0, int limit, int lane, int lrow) {
   constexpr int OLD = 136;
-  const int hh = lane >> 5, lrow = lane & 31;
+  const int hh = lane >> 5;
 #pragma unroll
   for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
@@ -487,6 +493,11 @@ __device__ __forceinline__ void store_rows_T(const f32x16_t (&acc)[4], float mul
   }
   __builtin_amdgcn_s_waitcnt(0xc07f);
   __builtin_amdgcn_wave_barrier();
+}
+
+__device__ __forceinline__ void store_rows_T(const f32x16_t (&acc)[4], float mul, bf16_t* stage, bf16_t* out,
+                                             int64_t ld_out, int row0, int limit, int lane) {
+  store_rows_T(acc, mul, stage, out, ld_out, row0, limit, lane, lane & 31);
 }
 
 // Inverse rotary rotation of a wavefront's transposed accumulators X^T[128 d][32 rows] in place, for
@@ -558,10 +569,32 @@ __global__ void __launch_bounds__(256) attn_bwd_prep_kernel(const bf16_t* __rest
 constexpr int kKvOffRing = 65536;                                        // key tile [256][128] bf16 in front of the ring
 constexpr int kKvStage = 2 * kTileBytes + 2 * 64 * 4;                    // Q tile | dO tile | lse[64] | D[64]
 constexpr size_t kKvLds = kKvOffRing + 2 * kKvStage;
+//
+// STORE_DS: every dS block this kernel forms is also written to memory (bf16, exactly what the dK product multiplies by) for
+// a dQ kernel that then needs one matrix product instead of three (attn_bwd_dq_stored_kernel).  Layout of `ds`, per (batch,
+// head): for block ib of 256 query rows, and in it for each 32-row group s (the rows of one wavefront of the dQ kernel),
+// the units of the key groups g = 0 .. 8 (ib + 1) - 1 one after the other (ds_unit_offset).  A unit is what one wavefront
+// here holds after one block: dS[32 rows][32 keys], 2 KiB, as 128 slots of 16 bytes.  Lane (key kk, lane half hh) holds the
+// two pieces tt = 0, 1 = accumulator registers 8 tt .. 8 tt + 7 = query rows 16 tt + 4 hh + {0..3, 8..11} of the group
+// (ds_row_of_slot gives the row for the position 16 hh + 8 tt + e the dQ kernel sees it at).  Piece tt goes to slot
+// ds_slot(kk, hh, tt): the 64 lanes of one store instruction fill one contiguous KiB, and the dQ kernel, which copies
+// units into LDS as they are, reads them back by transposing reads without bank conflicts (the 16 slots one half-wavefront
+// reads - 4 keys x 2 lane halves x 2 pieces - differ in their low 4 bits).  Blocks of queries in front of the keys are
+// never written and never read.
+// The stores cost this kernel 13 % (16.3 instead of 14.4 ms at S = 32768, 32 heads) wherever in the loop they are issued,
+// whether the next iteration's wait for loads also waits for them or not, and whether they go to 35 GB of memory or
+// over and over to the same few KiB: it is the issue of the store instructions that costs, not the traffic.
+constexpr int64_t kDsBlockBytes = 256 * 256 * 2;       // one (256 keys, 256 query rows) block
+__host__ __device__ inline int64_t ds_block_offset(int ib) { return (int64_t)ib * (ib + 1) / 2 * kDsBlockBytes; }     // blocks 0 .. ib-1 hold 256 (i + 1) keys each
+__host__ __device__ inline int64_t ds_unit_offset(int ib, int s, int g) { return ds_block_offset(ib) + ((int64_t)s * 8 * (ib + 1) + g) * 2048; }
+__device__ __forceinline__ unsigned ds_slot(int kk, int hh, int tt) { return (unsigned)(tt * 64 + ((((kk >> 2) * 8) + (kk & 3) * 2 + hh) ^ (tt * 8))); }
+__device__ __forceinline__ int ds_row_of_slot(int slot) { return 16 * ((slot >> 3) & 1) + 4 * (slot >> 4) + (slot & 3) + 8 * ((slot >> 2) & 1); }
+
+template <bool STORE_DS>
 __global__ void __launch_bounds__(kThreads8, 1)
 attn_bwd_dkv_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dO, const float* __restrict__ lse2,
                     const float* __restrict__ Dsum, bf16_t* __restrict__ dqkv, int B, int S, int Sp, int nh, float scale,
-                    const float* __restrict__ rope) {
+                    const float* __restrict__ rope, unsigned char* __restrict__ ds, int64_t ds_pair_bytes) {
   constexpr int BKVW = 256, BQ = 64, NS = 2;
   constexpr int kStage = kKvStage;
   constexpr int kA = 1;                                // fragment reads run this many MFMA steps ahead of their use (deeper costs registers this kernel does not have)
@@ -622,7 +655,7 @@ attn_bwd_dkv_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ d
     for (int r = 0; r < 16; ++r) { dk[dt][r] = 0.f; dv[dt][r] = 0.f; }
   const int kvi = kv0w + (lane & 31);
   const unsigned knat_t = la.nat + lds0 + wave * 8192;
-
+  unsigned char* const ds_pair = STORE_DS ? ds + (int64_t)bh * ds_pair_bytes : nullptr;
   for (int t = 0; t < nblk; ++t) {
     wait_vmcnt<0>();                                     // block t (issued one iteration ago) has landed
     stage_barrier();
@@ -685,6 +718,14 @@ attn_bwd_dkv_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ d
         }
 #pragma unroll
         for (int tt = 0; tt < 2; ++tt) { pb[tt] = pack8(sacc, tt); dsb[tt] = pack8(pacc, tt); }
+        if constexpr (STORE_DS) {
+          unsigned char* unit = ds_pair + ds_unit_offset(qrow0 >> 8, (qrow0 >> 5) & 7, kv0w >> 5);      // wavefront-uniform
+          int ln = lane;
+          asm volatile("" : "+v"(ln));                     // the slot numbers are made here, from the lane id, not kept in registers through the loop
+          // non-temporal: written once, read once by the next kernel, and 35 GB of it at S = 32768: nothing to keep in a cache
+          __builtin_nontemporal_store(dsb[0], reinterpret_cast<bf16x8_t*>(unit + ds_slot(ln & 31, ln >> 5, 0) * 16u));
+          __builtin_nontemporal_store(dsb[1], reinterpret_cast<bf16x8_t*>(unit + ds_slot(ln & 31, ln >> 5, 1) * 16u));
+        }
       }
       {
         bf16x8_t fq[8], fdo[8];
@@ -867,6 +908,122 @@ attn_bwd_dq_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dO
     rope_inverse_T(dq, rope, q0w + (ln & 31), S, ln);
   }
   store_rows_T(dq, scale, stage, dqout, ld, q0w, S, lane);
+}
+
+// =============================================================================== backward: dQ from stored dS
+// dQ^T[d][q] += K^T[d][kv] dS^T[kv][q] with dS read back from what attn_bwd_dkv_kernel<true> wrote: one product per (query
+// block, key block) pair instead of three, paid for with S^2 bytes per (batch, head) written once and read once.  Same
+// workgroup shape as the kernel above (256 query rows, wavefront w owns the 32-row group w), keys in tiles of 64 through a
+// 3-stage ring filled by direct global->LDS loads two tiles ahead: the K tile [64][128], shared, and per wavefront the two
+// dS units (32 keys each) of its own row group, 4 KiB copied as they lie in memory (consecutive tiles are consecutive
+// there: eight sequential streams per workgroup).  Both operands are transposing reads: K^T as in the kernel above, dS^T
+// from the wavefront's units at the slots ds_slot() gave them.  The 32 rows of a group come in the order the dK/dV kernel's
+// accumulators had them (ds_row_of_slot); only the epilogue needs to know.  With 16 MFMAs per wavefront and 48 KiB per
+// tile the kernel is bound by the rate the dS matrix streams in from memory.
+constexpr int kDqsStage = kTileBytes + 8 * 4096;       // K tile | 8 wavefronts x (2 units of 2 KiB)
+constexpr int kDqsStages = 3;
+constexpr size_t kDqsLds = (size_t)kDqsStages * kDqsStage;       // 144 KiB
+static_assert(kDqsLds <= 160 * 1024, "LDS budget");
+__global__ void __launch_bounds__(kThreads8, 1)
+attn_bwd_dq_stored_kernel(const bf16_t* __restrict__ qkv, const unsigned char* __restrict__ ds, int64_t ds_pair_bytes,
+                          bf16_t* __restrict__ dqkv, int B, int S, int nh, float scale, const float* __restrict__ rope) {
+  constexpr int BQ = 256, WQ = 32, BKV = 64, NS = kDqsStages;
+  constexpr int kStage = kDqsStage;
+  extern __shared__ __attribute__((aligned(256))) unsigned char lds_raw[];
+  const lds_u8_t* L = (const lds_u8_t*)lds_raw;
+  const unsigned lds0 = (unsigned)(size_t)L;
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  LaneAddr la;
+  la.init(lane);
+  const int nqt = (S + BQ - 1) / BQ;
+  int bh, rank;
+  pair_tile_of_block<false>((int)blockIdx.x, B * nh, nqt, bh, rank);
+  const int qt = nqt - 1 - rank;
+  const int b = bh / nh, h = bh % nh;
+  const int64_t H = (int64_t)nh * D, ld = 3 * H;
+  const bf16_t* qbase = qkv + (int64_t)b * S * ld + (int64_t)h * D;
+  const uint64_t kbase = (uint64_t)(qbase + H);
+  // this wavefront's units of block qt, key group 0 first: 2 KiB per key group, 8 (qt + 1) of them
+  const uint64_t dsbase = (uint64_t)(ds + (int64_t)bh * ds_pair_bytes + ds_unit_offset(qt, wave, 0));
+  const unsigned ldb = (unsigned)(ld * 2);
+  const int q0 = qt * BQ, q0w = q0 + wave * WQ;
+
+  const int kv_end = (q0 + BQ < S) ? q0 + BQ : S;
+  const int nkv = (kv_end + BKV - 1) / BKV;               // key groups 0 .. 2 nkv - 1 <= 8 (qt + 1) - 1: every unit read exists
+  auto issue = [&](int t, int stage) {
+    const unsigned st = lds0 + stage * kStage;
+    tile_dma(kbase, ldb, t * BKV, S, st, lane, wave);
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      lds_dma16_nt(dsbase, (unsigned)(t * 4096 + i * 1024 + lane * 16), st + kTileBytes + wave * 4096 + i * 1024);      // (6.0 instead of 6.8 ms at S = 32768)
+  };
+  for (int t = 0; t < NS - 1 && t < nkv; ++t) issue(t, t);
+
+  f32x16_t dq[4];
+#pragma unroll
+  for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) dq[dt][r] = 0.f;
+  // Transposing read of fragment T (keys 16 T + 8 rr + 4 h + (i >> 2), rr = 0, 1) of a unit: lane (blk = lane >> 4,
+  // i = lane & 15) reads 8 bytes = 4 consecutive positions 16 (blk & 1) + 4 (i & 3) .. of its key, which lie in piece
+  // tt = (i >> 1) & 1 of lane half blk & 1, at bytes 8 (i & 1) of the slot; T and rr add 512 T + 256 rr (they move the
+  // key by whole groups of four: bits 4, 5 of the slot number, clear of the XOR).
+  unsigned trd;
+  {
+    const int blk = lane >> 4, i = lane & 15;
+    trd = ds_slot(4 * (blk >> 1) + (i >> 2), blk & 1, (i >> 1) & 1) * 16u + 8u * (i & 1) + (unsigned)kTileBytes + (unsigned)wave * 4096u;
+  }
+
+  int stage = 0, stage_in = NS - 1;                     // stage of tile j; stage the next issue goes into
+  for (int j = 0; j < nkv; ++j) {
+    // 6 loads per tile and wavefront; tiles j and j + 1 are in flight here (issued two ahead)
+    if (j + 1 < nkv) wait_vmcnt<6>(); else wait_vmcnt<0>();
+    stage_barrier();                                    // the K tile j is visible; everybody is done with tile j - 1, whose stage tile j + 2 takes
+    if (j + NS - 1 < nkv) issue(j + NS - 1, stage_in);
+    const unsigned so = lds0 + stage * kStage;
+    stage = stage + 1 == NS ? 0 : stage + 1;
+    stage_in = stage_in + 1 == NS ? 0 : stage_in + 1;
+    const int kv0 = j * BKV;
+    if (kv0 > q0w + WQ - 1) continue;                   // every key of the tile lies behind this wavefront's rows: dS = 0, never written
+    const unsigned tr_t = la.tr + so, trd_t = trd + so;
+    static_for<2>([&](auto kb_c) {
+      TAW_CONST(kb, kb_c);
+      if (kv0 + kb * 32 > q0w + WQ - 1) return;         // wavefront-uniform; same for this half of the tile
+      constexpr int kAheadK = 3;
+      typedef s16x4_t __attribute__((address_space(3)))* lds_tr_t;
+      bf16x8_t fk[8];
+      union { s16x4_t h2[2]; bf16x8_t v; } dsb[2];
+#pragma unroll
+      for (int T = 0; T < 2; ++T)
+#pragma unroll
+        for (int rr = 0; rr < 2; ++rr)
+          dsb[T].h2[rr] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(reinterpret_cast<lds_tr_t>(trd_t + kb * 2048 + 512 * T + 256 * rr));
+      auto rd = [&](auto i_c) {
+        TAW_CONST(i, i_c);
+        bf16x8_t un2;
+        frag_tr2x2<i / 4, i % 4, kb * 8192, -1>(tr_t, fk[i], un2);
+      };
+      static_for<kAheadK>(rd);
+      __builtin_amdgcn_s_setprio(1);
+      static_for<8>([&](auto i_c) {
+        TAW_CONST(i, i_c);
+        if constexpr (i + kAheadK < 8) rd(std::integral_constant<int, i + kAheadK>{});
+        __builtin_amdgcn_sched_barrier(0);
+        dq[i % 4] = mfma(fk[i], dsb[i / 4].v, dq[i % 4]);
+        __builtin_amdgcn_sched_barrier(0);
+      });
+      __builtin_amdgcn_s_setprio(0);
+    });
+  }
+  __syncthreads();          // the ring becomes the output staging area
+
+  bf16_t* stage_out = reinterpret_cast<bf16_t*>(lds_raw) + wave * (32 * 136);
+  bf16_t* dqout = dqkv + (int64_t)b * S * ld + (int64_t)h * D;
+  const int lrow = ds_row_of_slot(lane & 31);           // the query row (of the wavefront's 32) this lane's column of dQ^T is
+  if (rope) rope_inverse_T(dq, rope, q0w + lrow, S, lane);
+  store_rows_T(dq, scale, stage_out, dqout, ld, q0w, S, lane, lrow);
 }
 
 // =============================================================================== backward: dK, dV and dQ in one kernel
@@ -1287,10 +1444,19 @@ int attn_bwd_slots(int B, int S, int nh) {
   return best;
 }
 
-size_t attn_bwd_mfma_scratch_floats(int B, int S, int nh, bool with_slots) {
+// bytes of stored dS per (batch, head): block ib of 256 query rows holds 256 (ib + 1) keys x 256 rows bf16
+static int64_t attn_bwd_ds_pair_bytes(int S) { return ds_block_offset((S + 255) / 256); }
+
+size_t attn_bwd_mfma_scratch_floats(int B, int S, int nh, int form) {
   const size_t prep = 2 * (size_t)B * nh * ((S + 63) / 64 * 64);
-  if (!with_slots) return prep;
-  return prep + (size_t)attn_bwd_slots(B, S, nh) * (size_t)B * S * nh * D;      // one slot suffices for the atomic form
+  const size_t slots = (size_t)attn_bwd_slots(B, S, nh) * (size_t)B * S * nh * D;      // one slot suffices for the atomic form
+  const size_t stored = (size_t)B * nh * (size_t)attn_bwd_ds_pair_bytes(S) / 4;
+  switch (form) {
+    case ATTN_BWD_SPLIT: return prep;
+    case ATTN_BWD_FUSED: case ATTN_BWD_FUSED_ATOMIC: return prep + slots;
+    case ATTN_BWD_STORED: return prep + stored;
+    default: return prep + (slots > stored ? slots : stored);                           // enough for every form
+  }
 }
 
 int launch_attn_bwd_mfma(int B, int S, int nh, const void* qkv, const void* o, const void* dO, const float* lse, float* prep,
@@ -1333,13 +1499,30 @@ int launch_attn_bwd_mfma(int B, int S, int nh, const void* qkv, const void* o, c
                        (int)H, scale, rope_table);
     return (int)hipGetLastError();
   }
+  if (form == ATTN_BWD_STORED) {
+    // the stored dS follows the row statistics (a multiple of 512 bytes in front of it)
+    unsigned char* ds = reinterpret_cast<unsigned char*>(slots);
+    const int64_t pair_bytes = attn_bwd_ds_pair_bytes(S);
+    constexpr size_t lds = kKvLds;
+    TAW_SET_LDS_LIMIT_ONCE(attn_bwd_dkv_kernel<true>, lds);
+    const int nkt = (S + 255) / 256;
+    hipLaunchKernelGGL(attn_bwd_dkv_kernel<true>, dim3((unsigned)(nkt * B * nh)), dim3(kThreads8), lds, st, (const bf16_t*)qkv, (const bf16_t*)dO, lse2,
+                       Dv, (bf16_t*)dqkv, B, S, Sp, nh, scale, rope_table, ds, pair_bytes);
+    int rc = (int)hipGetLastError();
+    if (rc) return rc;
+    static_assert(kDqsLds >= 8 * 32 * 136 * sizeof(bf16_t), "staging area");
+    TAW_SET_LDS_LIMIT_ONCE(attn_bwd_dq_stored_kernel, kDqsLds);
+    hipLaunchKernelGGL(attn_bwd_dq_stored_kernel, dim3((unsigned)(nkt * B * nh)), dim3(kThreads8), kDqsLds, st, (const bf16_t*)qkv, ds, pair_bytes,
+                       (bf16_t*)dqkv, B, S, nh, scale, rope_table);
+    return (int)hipGetLastError();
+  }
   {
     constexpr size_t lds = kKvLds;
     static_assert(lds >= 8 * 32 * 136 * sizeof(bf16_t), "staging area");
-    TAW_SET_LDS_LIMIT_ONCE(attn_bwd_dkv_kernel, lds);
+    TAW_SET_LDS_LIMIT_ONCE(attn_bwd_dkv_kernel<false>, lds);
     const int nkt = (S + 255) / 256;
-    hipLaunchKernelGGL(attn_bwd_dkv_kernel, dim3((unsigned)(nkt * B * nh)), dim3(kThreads8), lds, st, (const bf16_t*)qkv, (const bf16_t*)dO, lse2, Dv,
-                       (bf16_t*)dqkv, B, S, Sp, nh, scale, rope_table);
+    hipLaunchKernelGGL(attn_bwd_dkv_kernel<false>, dim3((unsigned)(nkt * B * nh)), dim3(kThreads8), lds, st, (const bf16_t*)qkv, (const bf16_t*)dO, lse2, Dv,
+                       (bf16_t*)dqkv, B, S, Sp, nh, scale, rope_table, nullptr, (int64_t)0);
     int rc = (int)hipGetLastError();
     if (rc) return rc;
   }

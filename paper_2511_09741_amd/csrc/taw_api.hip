@@ -65,7 +65,8 @@ static int check_desc(const taw_layer_desc* d) {
   if ((int64_t)d->B * d->S > (int64_t)1 << 24) return fail(TAW_ERR_SHAPE, "B*S=%lld exceeds 2^24 tokens", (long long)d->B * d->S);
   if (!(d->rms_eps >= 0.f)) return fail(TAW_ERR_SHAPE, "rms_eps must be >= 0");
   if (!(d->rope_theta > 0.f)) return fail(TAW_ERR_SHAPE, "rope_theta must be > 0");
-  if (d->flags & ~(TAW_ACCUMULATE | TAW_RECOMPUTE | TAW_ATTN_BWD_FUSED)) return fail(TAW_ERR_SHAPE, "unknown flag bits 0x%x", d->flags);
+  if (d->flags & ~(TAW_ACCUMULATE | TAW_RECOMPUTE | TAW_ATTN_BWD_FUSED | TAW_ATTN_BWD_RECOMPUTE)) return fail(TAW_ERR_SHAPE, "unknown flag bits 0x%x", d->flags);
+  if ((d->flags & TAW_ATTN_BWD_FUSED) && (d->flags & TAW_ATTN_BWD_RECOMPUTE)) return fail(TAW_ERR_SHAPE, "TAW_ATTN_BWD_FUSED and TAW_ATTN_BWD_RECOMPUTE name two different forms");
   return TAW_OK;
 }
 
@@ -127,6 +128,11 @@ static size_t linear_bwd_scratch_floats(int64_t T, int64_t N, int64_t K) {
   return sp > 1 ? (size_t)sp * (size_t)N * (size_t)K : 0;
 }
 
+// which form of the MFMA attention backward the layer runs
+static int attn_bwd_form_of(const taw_layer_desc* d) {
+  return (d->flags & TAW_ATTN_BWD_FUSED) ? ATTN_BWD_FUSED : (d->flags & TAW_ATTN_BWD_RECOMPUTE) ? ATTN_BWD_SPLIT : ATTN_BWD_STORED;
+}
+
 static Ctx carve_ctx(const taw_layer_desc* d, void* base) {
   const size_t e = dt_size(d->dtype), T = (size_t)d->B * d->S, H = d->H, I = d->I;
   Carve c(base); Ctx x;
@@ -142,7 +148,7 @@ static Work carve_work(const taw_layer_desc* d, void* base) {
   Carve c(base); Work w;
   w.da = c.take(T * I * e); w.dgu = c.take(T * 2 * I * e); w.dhn = c.take(T * H * e); w.dh = c.take(T * H * e);
   w.dO = c.take(T * H * e); w.dqkv = c.take(T * 3 * H * e); w.dxn = c.take(T * H * e);
-  w.D = (float*)c.take(attn_bwd_mfma_scratch_floats(d->B, d->S, d->n_heads, (d->flags & TAW_ATTN_BWD_FUSED) != 0) * 4);   // covers the generic kernel's B*nh*S too
+  w.D = (float*)c.take(attn_bwd_mfma_scratch_floats(d->B, d->S, d->n_heads, attn_mfma_supported(d->dtype, d->S, d->n_heads, d->head_dim) ? attn_bwd_form_of(d) : ATTN_BWD_SPLIT) * 4);   // covers the generic kernel's B*nh*S too
   w.partials = (float*)c.take((size_t)rmsnorm_bwd_partial_rows() * H * 4);
   size_t sk = linear_bwd_scratch_floats((int64_t)T, (int64_t)H, (int64_t)I);                  // down
   sk = std::max(sk, linear_bwd_scratch_floats((int64_t)T, (int64_t)(2 * I), (int64_t)H));     // gate, up
@@ -305,7 +311,7 @@ extern "C" int taw_layer_bwd(const taw_layer_desc* desc, const void* W_chunk, co
   // attention backward, then the rotary backward on dq, dk (the MFMA kernels apply it to their accumulators before storing)
   if (p.mfma_attn) {
     TAW_LAUNCH(launch_attn_bwd_mfma(desc->B, desc->S, desc->n_heads, c.qkv, c.o, w.dO, c.lse, w.D, w.dqkv, rope_table,
-                                    (desc->flags & TAW_ATTN_BWD_FUSED) ? ATTN_BWD_FUSED : ATTN_BWD_SPLIT, st), "attention bwd (mfma)");
+                                    attn_bwd_form_of(desc), st), "attention bwd (mfma)");
   } else {
     TAW_LAUNCH(launch_attn_rowdot(dt, desc->B, desc->S, desc->n_heads, desc->head_dim, c.o, H, w.dO, H, w.D, st), "attention row dot");
     TAW_LAUNCH(launch_attn_bwd_generic(dt, desc->B, desc->S, desc->n_heads, desc->head_dim, c.qkv, w.dO, c.lse, w.D, w.dqkv, st), "attention bwd (generic)");
@@ -522,7 +528,7 @@ static int check_attn(int32_t dtype, int32_t B, int32_t S, int32_t nh, int32_t d
   int rc = check_dtype(dtype);
   if (rc) return rc;
   if (B <= 0 || S <= 0 || nh <= 0 || d <= 0 || d % 2) return fail(TAW_ERR_SHAPE, "bad attention shape (B=%d S=%d n_heads=%d head_dim=%d)", B, S, nh, d);
-  if (impl < TAW_IMPL_AUTO || impl > TAW_IMPL_MFMA_ATOMIC) return fail(TAW_ERR_SHAPE, "unknown impl %d", impl);
+  if (impl < TAW_IMPL_AUTO || impl > TAW_IMPL_MFMA_STORED) return fail(TAW_ERR_SHAPE, "unknown impl %d", impl);
   const bool can = attn_mfma_supported(dtype, S, nh, d);
   if (impl >= TAW_IMPL_MFMA && !can) return fail(TAW_ERR_UNSUPPORTED, "MFMA attention needs bf16 and head_dim 128");
   *use_mfma = can && impl != TAW_IMPL_GENERIC;
@@ -545,7 +551,7 @@ extern "C" int taw_op_attn_fwd(int32_t dtype, int32_t B, int32_t S, int32_t n_he
 
 extern "C" size_t taw_op_attn_bwd_scratch_floats(int32_t B, int32_t S, int32_t n_heads) {
   if (B <= 0 || S <= 0 || n_heads <= 0) return 0;
-  return attn_bwd_mfma_scratch_floats(B, S, n_heads, true);
+  return attn_bwd_mfma_scratch_floats(B, S, n_heads, ATTN_BWD_ANY);
 }
 
 extern "C" int taw_op_attn_bwd(int32_t dtype, int32_t B, int32_t S, int32_t n_heads, int32_t head_dim, const void* qkv, const void* o,
@@ -560,7 +566,7 @@ extern "C" int taw_op_attn_bwd(int32_t dtype, int32_t B, int32_t S, int32_t n_he
   const hipStream_t st = (hipStream_t)stream;
   const int64_t H = (int64_t)n_heads * head_dim;
   if (mf) {
-    const int form = impl == TAW_IMPL_MFMA_FUSED ? ATTN_BWD_FUSED : impl == TAW_IMPL_MFMA_ATOMIC ? ATTN_BWD_FUSED_ATOMIC : ATTN_BWD_SPLIT;
+    const int form = impl == TAW_IMPL_MFMA_FUSED ? ATTN_BWD_FUSED : impl == TAW_IMPL_MFMA_ATOMIC ? ATTN_BWD_FUSED_ATOMIC : impl == TAW_IMPL_MFMA_STORED ? ATTN_BWD_STORED : ATTN_BWD_SPLIT;
     TAW_LAUNCH(launch_attn_bwd_mfma(B, S, n_heads, qkv, o, dO, lse, scratch, dqkv, rope_table, form, st), "attention bwd (mfma)");
   } else {
     TAW_LAUNCH(launch_attn_rowdot(dtype, B, S, n_heads, head_dim, o, H, dO, H, scratch, st), "attention row dot");

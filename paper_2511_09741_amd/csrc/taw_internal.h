@@ -130,12 +130,12 @@ int launch_attn_fwd_mfma(int B, int S, int nh, const void* qkv, void* o, float* 
 // sums them: no atomics, reproducible.  FUSED_ATOMIC: the fused kernel adding dQ with fp32 atomics into one buffer.
 // On this part the split pair is the fastest (S = 32768, 32 heads: 26.7 ms against 30.4 and 27.2): the atomic units
 // take 25.4 ms for the adds alone, and the slots move 69 GB through HBM that the recomputation does not.
-enum { ATTN_BWD_SPLIT = 0, ATTN_BWD_FUSED = 1, ATTN_BWD_FUSED_ATOMIC = 2 };
+enum { ATTN_BWD_SPLIT = 0, ATTN_BWD_FUSED = 1, ATTN_BWD_FUSED_ATOMIC = 2, ATTN_BWD_STORED = 3, ATTN_BWD_ANY = -1 };
 // workers (and fp32 dQ slots) per (batch, head) the fused form uses for this shape
 int attn_bwd_slots(int B, int S, int nh);
 // fp32 scratch of the MFMA backward: scaled lse and D, each padded to a multiple of 64 rows per (batch, head); with_slots:
 // followed by the dQ slots of the fused forms
-size_t attn_bwd_mfma_scratch_floats(int B, int S, int nh, bool with_slots);
+size_t attn_bwd_mfma_scratch_floats(int B, int S, int nh, int form);
 // computes its own row statistics (scratch) from o, dO and lse.  rope_table != nullptr: q and k were rotated
 // (table [S, 64, 2] fp32 of cos, sin) and dq, dk come out as gradients of the unrotated q, k
 int launch_attn_bwd_mfma(int B, int S, int nh, const void* qkv, const void* o, const void* dO, const float* lse,

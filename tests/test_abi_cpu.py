@@ -65,11 +65,12 @@ def test_weight_layout_matches_the_papers_parameter_count(lib):
 
 
 def test_ctx_and_workspace_sizes(lib):
-    d = taw.desc_from_config(I.CONFIGS["C3"])
+    d = taw.desc_from_config(I.CONFIGS["C3"], taw.TAW_ATTN_BWD_RECOMPUTE)      # without the dS hand-over of the default attention backward
     ctx, ws = taw.taw_layer_ctx_bytes(d), taw.taw_layer_workspace_bytes(d)
     T, H, I_ = 32768, 4096, 11008
     assert ctx >= 2 * T * (7 * H + 3 * I_) and ctx < 5 * 2**30
     assert ws >= 2 * T * (7 * H + 3 * I_) and ws < 5 * 2**30
+    assert taw.taw_layer_ctx_bytes(taw.desc_from_config(I.CONFIGS["C3"])) == ctx
     bad = taw.make_desc(1, 1, 128, 100, 3, 32, 64)
     assert taw.taw_layer_ctx_bytes(bad) == 0 and taw.taw_layer_workspace_bytes(bad) == 0
 
@@ -90,7 +91,7 @@ def test_recompute_mode_moves_the_cache_into_the_workspace(lib):
 @pytest.mark.parametrize("kw,code", [
     (dict(H=100), taw.TAW_ERR_SHAPE), (dict(S=0), taw.TAW_ERR_SHAPE), (dict(B=-1), taw.TAW_ERR_SHAPE),
     (dict(dtype=7), taw.TAW_ERR_DTYPE), (dict(head_dim=15, n_heads=4, H=60), taw.TAW_ERR_SHAPE),
-    (dict(flags=8), taw.TAW_ERR_SHAPE), (dict(rope_theta=0.0), taw.TAW_ERR_SHAPE),
+    (dict(flags=16), taw.TAW_ERR_SHAPE), (dict(flags=4 | 8), taw.TAW_ERR_SHAPE), (dict(rope_theta=0.0), taw.TAW_ERR_SHAPE),
 ])
 def test_bad_descriptors_are_rejected(lib, kw, code):
     base = dict(dtype=0, B=1, S=128, H=64, n_heads=4, head_dim=16, I=176)
@@ -278,3 +279,17 @@ def test_linear_bwd_scratch_rule(lib):
         assert 2 <= splits <= 32 and T // splits >= 512 - 64
     for T, N, K in ((0, 8, 8), (8, 0, 8), (-1, 8, 8), (256, 256, 256), (1023, 8, 8)):
         assert f(T, N, K) == 0
+
+
+def test_workspace_size_follows_the_attention_backward_form(lib):
+    """The default backward hands dS over through the workspace: S * S bytes per (batch, head), counted in blocks of 256
+    (sum over query blocks ib of 256 (ib + 1) keys x 256 rows x 2 bytes); TAW_ATTN_BWD_RECOMPUTE needs none of it; layers
+    that cannot take the matrix-core attention (fp32, or heads other than 128) never pay for it."""
+    for name in ("C2", "C3", "C4", "C5"):
+        cfg = I.CONFIGS[name]
+        full = taw.taw_layer_workspace_bytes(taw.desc_from_config(cfg, 0))
+        lean = taw.taw_layer_workspace_bytes(taw.desc_from_config(cfg, taw.TAW_ATTN_BWD_RECOMPUTE))
+        nqt = (cfg.S + 255) // 256
+        assert full - lean == cfg.B * cfg.n_heads * (nqt * (nqt + 1) // 2) * 256 * 256 * 2
+    c1 = I.CONFIGS["C1"]
+    assert taw.taw_layer_workspace_bytes(taw.desc_from_config(c1, 0)) == taw.taw_layer_workspace_bytes(taw.desc_from_config(c1, taw.TAW_ATTN_BWD_RECOMPUTE))

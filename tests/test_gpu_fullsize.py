@@ -237,12 +237,15 @@ def test_backward_linear_weight_gradient_cut_along_tokens(taw, T, N, K):
         assert e_dx < TOL and e_g < 1e-4
 
 
-@pytest.mark.parametrize("width,form", [(w, 2) for w in WIDTHS] + [("C3", 3), ("C4", 3)], ids=[w + "-split" for w in WIDTHS] + ["C3-fused", "C4-fused"])
+@pytest.mark.parametrize("width,form", [(w, 5) for w in WIDTHS] + [("C3", 2), ("C3", 3), ("C4", 3)],
+                         ids=[w + "-stored" for w in WIDTHS] + ["C3-split", "C3-fused", "C4-fused"])
 def test_attention_sampled(taw, width, form):
     """Attention at the layer's shape (all heads, all batch elements in one launch): o and lse at
     sampled (batch, head, row); dq, dk, dv on the last 300 positions, once as gradients of the q, k
-    passed in and once through the rotary backward (rope_table given).  The split backward (form 2, what
-    taw_layer_bwd runs) at every width, the fused form with dQ slots (form 3) at two (16 and 4 key blocks per worker)."""
+    passed in and once through the rotary backward (rope_table given).  The backward with stored dS (form 5, what
+    taw_layer_bwd runs) at every width, where it must also equal the pair that recomputes the scores bit for bit
+    over the whole of dq, dk, dv (the two contract in the same order); that pair (form 2) against the oracle at one width;
+    the fused form with dQ slots (form 3) at two (16 and 4 key blocks per worker)."""
     import torch
     cfg = I.CONFIGS[width]
     B, S, nh, d = cfg.B, cfg.S, cfg.n_heads, cfg.head_dim
@@ -260,6 +263,12 @@ def test_attention_sampled(taw, width, form):
     taw.taw_op_attn_bwd(BF, B, S, nh, d, qkv, o, dO, lse, dqkv, scratch, None, form)
     taw.taw_op_attn_bwd(BF, B, S, nh, d, qkv, o, dO, lse, dqkv_rot, scratch, table, form)
     torch.cuda.synchronize()
+    if form == 5:
+        other = torch.empty_like(qkv)
+        taw.taw_op_attn_bwd(BF, B, S, nh, d, qkv, o, dO, lse, other, scratch, table, 2)
+        torch.cuda.synchronize()
+        assert torch.equal(other, dqkv_rot)
+        del other
     rows = np.array([0, 1, 63, 64, 255, 256, 257, 8191, 8192, S // 2 + 3617, S - 1 - 256, S - 1])
     t0 = S - 300
     phi = O.rope_angles(S, d, cfg.rope_theta)

@@ -113,10 +113,10 @@ def test_bf16_layer_at_the_widths_of_the_papers_throughput_table(taw, H, nh, B, 
     U.check_layer(taw, cfg, seed=H + S)
 
 
-def test_bf16_layer_with_the_fused_attention_backward(taw):
-    """TAW_ATTN_BWD_FUSED: the layer's backward with the one-kernel attention backward (dQ partial sums in private
-    slots inside the workspace) against the oracle, and against the default pair of kernels (same tolerance; the two
-    differ in summation order only)."""
+def test_bf16_layer_with_the_other_forms_of_the_attention_backward(taw):
+    """TAW_ATTN_BWD_FUSED (one kernel, dQ partial sums in private slots inside the workspace) and TAW_ATTN_BWD_RECOMPUTE
+    (two kernels, the scores recomputed, nothing extra in the workspace) against the oracle, beside the default (two
+    kernels, dS handed over through the workspace); same tolerance, they differ in summation order at most."""
     cfg = I.LayerConfig("bf16-fused-bwd", I.BF16, 2, 1100, 512, 4, 128, 1408, sigma_w=0.05)
     w = I.make_weights(cfg, 7, gamma_jitter=0.1)
     x, dy = I.make_activations(cfg, 7)
@@ -124,8 +124,9 @@ def test_bf16_layer_with_the_fused_attention_backward(taw):
     from oracle import decoder_layer as O
     yr, cache = O.layer_fwd(w64, I.to_f64(x, cfg.dtype), cfg.n_heads, cfg.rope_theta, cfg.rms_eps)
     dxr, Gr = O.layer_bwd(w64, cache, I.to_f64(dy, cfg.dtype))
-    assert taw.taw_layer_workspace_bytes(taw.desc_from_config(cfg, taw.TAW_ATTN_BWD_FUSED)) > taw.taw_layer_workspace_bytes(taw.desc_from_config(cfg, 0))
-    for flags in (taw.TAW_ATTN_BWD_FUSED, 0):
+    ws = {f: taw.taw_layer_workspace_bytes(taw.desc_from_config(cfg, f)) for f in (0, taw.TAW_ATTN_BWD_FUSED, taw.TAW_ATTN_BWD_RECOMPUTE)}
+    assert ws[taw.TAW_ATTN_BWD_RECOMPUTE] < ws[0] and ws[taw.TAW_ATTN_BWD_RECOMPUTE] < ws[taw.TAW_ATTN_BWD_FUSED]
+    for flags in (taw.TAW_ATTN_BWD_FUSED, taw.TAW_ATTN_BWD_RECOMPUTE, 0):
         L = U.DeviceLayer(taw, cfg, flags=flags)
         L.set_weights(w)
         xd, dyd = U.to_dev(x, cfg.dtype), U.to_dev(dy, cfg.dtype)

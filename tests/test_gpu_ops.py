@@ -280,8 +280,9 @@ def test_gemm_mfma_fp32_output_is_accurate(taw):
         assert err < 2e-6, (mode, err)
 
 
-# the three forms of the MFMA backward: the split dK/dV + dQ pair (the default), fused with private dQ slots, fused with atomics
-BWD_FORMS = {"split": 2, "fused": 3, "atomic": 4}
+# the forms of the MFMA backward: the split dK/dV + dQ pair, fused with private dQ slots, fused with atomics, and the split
+# pair whose dK/dV kernel stores dS for the dQ kernel
+BWD_FORMS = {"split": 2, "fused": 3, "atomic": 4, "stored": 5}
 
 
 @pytest.mark.parametrize("form", list(BWD_FORMS))
@@ -299,8 +300,10 @@ def test_attention_mfma_peaked_scores(taw, form):
     _attn_case(taw, I.BF16, 1, 700, 2, 128, taw.TAW_IMPL_MFMA, seed=9, scale=3.0, bwd_impl=BWD_FORMS[form])
 
 
-def test_attention_backward_fused_form_is_reproducible(taw):
-    """The fused backward with slots adds its dQ partial sums in a fixed order (no atomics): two runs give the same bits."""
+@pytest.mark.parametrize("form", ["fused", "stored"])
+def test_attention_backward_forms_without_atomics_are_reproducible(taw, form):
+    """The fused backward with slots adds its dQ partial sums in a fixed order, and the form with stored dS reads back only
+    what it wrote: two runs over scratch with different stale contents give the same bits."""
     import torch
     B, S, nh, d = 2, 1500, 3, 128
     H = nh * d
@@ -313,7 +316,7 @@ def test_attention_backward_fused_form_is_reproducible(taw):
     for fill in (0.0, 1e30):
         scratch = torch.full((taw.taw_op_attn_bwd_scratch_floats(B, S, nh),), fill, dtype=torch.float32, device="cuda")   # stale contents must not matter
         dqkv = torch.empty_like(qkv)
-        taw.taw_op_attn_bwd(I.BF16, B, S, nh, d, qkv, o, dO, lse, dqkv, scratch, None, taw.TAW_IMPL_MFMA_FUSED)
+        taw.taw_op_attn_bwd(I.BF16, B, S, nh, d, qkv, o, dO, lse, dqkv, scratch, None, BWD_FORMS[form])
         torch.cuda.synchronize()
         outs.append(dqkv)
     assert torch.equal(outs[0], outs[1])
