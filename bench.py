@@ -63,7 +63,7 @@ PEAK_HBM_GBS = 8000.0
 TRAFFIC_BYTES_PER_LAUNCH = {
     ("C2", "gemm"): (1442.9e6, "profiles/gemm_C2_hbm_traffic.md"),
     ("C3", "gemm"): (5424.2e6, "profiles/attn_C3_kernels.md"),
-    ("C3", "attn_bwd"): (15.37e9, "profiles/attn_C3_kernels.md"),
+    ("C3", "attn_bwd"): (81.1e9, "profiles/attn_C3_kernels.md"),
 }
 # the paper's throughput table (Experiments, Throughput and Memory Usage): micro-batch size per sequence length and
 # TawPipe's tokens per GPU per second on its own hardware
