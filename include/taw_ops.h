@@ -22,12 +22,13 @@ extern "C" {
 #endif
 
 enum { TAW_IMPL_AUTO = 0, TAW_IMPL_GENERIC = 1, TAW_IMPL_MFMA = 2,
-       /* taw_op_attn_bwd only: the two fused forms of the MFMA backward.  TAW_IMPL_MFMA is the split pair (a dK/dV kernel
-          and a dQ kernel that each recompute the scores: 7 matrix products per tile pair), which is the fastest on
-          this part; the fused kernel forms the scores once (5 products) and pays for it in dQ traffic. */
-       TAW_IMPL_MFMA_FUSED = 3,   /* dQ partial sums in private fp32 slots, one per worker, summed by a last pass: no atomics, reproducible */
-       TAW_IMPL_MFMA_ATOMIC = 4,  /* dQ added with fp32 atomics into one buffer (not bit-reproducible) */
-       TAW_IMPL_MFMA_STORED = 5   /* the dK/dV kernel also writes dS (bf16) to the scratch and the dQ kernel reads it back: 5 products, no atomics, reproducible */ };
+       /* taw_op_attn_bwd only: the forms of the MFMA backward.  TAW_IMPL_MFMA is the pair of kernels (dK/dV, then dQ) that
+          each recompute the scores: 7 matrix products per tile pair, nothing but the row statistics in the scratch.
+          TAW_IMPL_AUTO takes TAW_IMPL_MFMA_STORED where the MFMA kernels apply, as taw_layer_bwd does by default. */
+       TAW_IMPL_MFMA_FUSED = 3,   /* one kernel, 5 products; dQ partial sums in private fp32 slots, one per worker, summed by a last pass: no atomics, reproducible */
+       TAW_IMPL_MFMA_ATOMIC = 4,  /* one kernel, 5 products; dQ added with fp32 atomics into one buffer (not bit-reproducible) */
+       TAW_IMPL_MFMA_STORED = 5   /* two kernels, 5 products: the dK/dV kernel also writes dS (bf16) to the scratch and the dQ kernel reads it
+                                     back instead of recomputing it; no atomics, same bits as TAW_IMPL_MFMA; the fastest on this part */ };
 enum { TAW_GEMM_NT = 0, TAW_GEMM_NN = 1, TAW_GEMM_TN = 2 };
 
 /* The three products of a linear layer y = x W^T (W is [out, in]):
@@ -89,8 +90,9 @@ int taw_op_attn_fwd(int32_t dtype, int32_t B, int32_t S, int32_t n_heads, int32_
  * backward, a rotation by the opposite angle, applied before the store); NULL leaves them as the
  * gradients of the q, k passed in.
  * scratch: fp32, taw_op_attn_bwd_scratch_floats(B, S, n_heads) elements, enough for every form: the row statistics
- * D[t] = dO[t].o[t] and a rescaled copy of lse, then (fused forms only) the fp32 partial sums of dq, one [B*S, H] slot
- * per worker of a (batch, head), the count chosen from the shape.  Contents are overwritten; the caller clears nothing. */
+ * D[t] = dO[t].o[t] and a rescaled copy of lse, then either (fused forms) the fp32 partial sums of dq, one [B*S, H] slot
+ * per worker of a (batch, head), the count chosen from the shape, or (TAW_IMPL_MFMA_STORED) dS in bf16, about S*S bytes
+ * per (batch, head).  Contents are overwritten; the caller clears nothing. */
 size_t taw_op_attn_bwd_scratch_floats(int32_t B, int32_t S, int32_t n_heads);
 int taw_op_attn_bwd(int32_t dtype, int32_t B, int32_t S, int32_t n_heads, int32_t head_dim, const void* qkv,
                     const void* o, const void* dO, const float* lse, void* dqkv, float* scratch,

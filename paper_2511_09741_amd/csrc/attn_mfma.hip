@@ -1027,7 +1027,7 @@ attn_bwd_dq_stored_kernel(const bf16_t* __restrict__ qkv, const unsigned char* _
 }
 
 // =============================================================================== backward: dK, dV and dQ in one kernel
-// Five matrix products per (query block, key block) pair instead of the seven of the split pair above: S and dP are formed
+// Five matrix products per (query block, key block) pair, like the pair of kernels with stored dS above, in one kernel: S and dP are formed
 // once, by the key-stationary side, and dQ is produced from the same dS.  The obstacle is the register layout: the
 // accumulators of S and dP give a lane one KEY column, and the matrix cores contract over registers, never over lanes, so
 // dQ[q][d] = sum_kv dS[q][kv] K[kv][d] cannot be fed from them.  Here dS crosses the workgroup through LDS:
@@ -1037,9 +1037,9 @@ attn_bwd_dq_stored_kernel(const bf16_t* __restrict__ qkv, const unsigned char* _
 //           split by OUTPUT: four wavefronts take one 32-column tile each and contract over all 256 keys (operands: dS from
 //           Ex^T and K from a copy of the key tile in LDS, both by transposing reads); the two wavefronts of a SIMD take
 //           turns, so every SIMD sees 80 MFMAs per block.
-// Where the dQ tile goes decides the kernel's speed, and on this part neither way beats the split pair, which is why that
-// pair stays the default (S = 32768, 32 heads: split 26.7 ms; this kernel 24.1 ms when it drops the dQ tiles, 27.2 ms
-// with atomics, 30.4 ms with slots):
+// Where the dQ tile goes decides the kernel's speed, and on this part neither way beats the pairs of kernels above, which
+// is why one of those is the default (S = 32768, 32 heads: 23.7 ms with stored dS, 25.8 ms recomputing; this kernel
+// 24.1 ms when it drops the dQ tiles, 27.6 ms with atomics, 30.9 ms with slots):
 //   kDqAtomic  fp32 atomic adds into one dQ buffer.  The atomic units retire 0.34 T adds/s, and a 256-key workgroup
 //              issues S^2/4 adds per head: 25.4 ms for the adds alone at that size.
 //   kDqSlots   a deterministic two-level split over key blocks without atomics: the key blocks of a (batch, head) are dealt

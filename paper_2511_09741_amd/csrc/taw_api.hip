@@ -566,7 +566,7 @@ extern "C" int taw_op_attn_bwd(int32_t dtype, int32_t B, int32_t S, int32_t n_he
   const hipStream_t st = (hipStream_t)stream;
   const int64_t H = (int64_t)n_heads * head_dim;
   if (mf) {
-    const int form = impl == TAW_IMPL_MFMA_FUSED ? ATTN_BWD_FUSED : impl == TAW_IMPL_MFMA_ATOMIC ? ATTN_BWD_FUSED_ATOMIC : impl == TAW_IMPL_MFMA_STORED ? ATTN_BWD_STORED : ATTN_BWD_SPLIT;
+    const int form = impl == TAW_IMPL_MFMA_FUSED ? ATTN_BWD_FUSED : impl == TAW_IMPL_MFMA_ATOMIC ? ATTN_BWD_FUSED_ATOMIC : impl == TAW_IMPL_MFMA ? ATTN_BWD_SPLIT : ATTN_BWD_STORED;
     TAW_LAUNCH(launch_attn_bwd_mfma(B, S, n_heads, qkv, o, dO, lse, scratch, dqkv, rope_table, form, st), "attention bwd (mfma)");
   } else {
     TAW_LAUNCH(launch_attn_rowdot(dtype, B, S, n_heads, head_dim, o, H, dO, H, scratch, st), "attention row dot");

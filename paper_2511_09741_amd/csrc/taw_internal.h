@@ -124,17 +124,20 @@ int launch_gemm_mfma_nt_rope(int64_t M, int64_t N, int64_t K, const void* A, int
 // bf16, head_dim 128, and S * 3 * n_heads * head_dim * 2 bytes below 4 GiB (32-bit row offsets inside one batch element)
 bool attn_mfma_supported(int dtype, int S, int nh, int d);
 int launch_attn_fwd_mfma(int B, int S, int nh, const void* qkv, void* o, float* lse, hipStream_t st);
-// The MFMA backward exists in three forms.  SPLIT (default): a dK/dV kernel and a dQ kernel that each recompute S and dP
-// (7 matrix products per tile pair), no atomics, reproducible.  FUSED: one key-stationary kernel forms S and dP once
-// and produces dK, dV and dQ (5 products); dQ partial sums go to private fp32 slots, one per worker, and a last pass
-// sums them: no atomics, reproducible.  FUSED_ATOMIC: the fused kernel adding dQ with fp32 atomics into one buffer.
-// On this part the split pair is the fastest (S = 32768, 32 heads: 26.7 ms against 30.4 and 27.2): the atomic units
-// take 25.4 ms for the adds alone, and the slots move 69 GB through HBM that the recomputation does not.
+// The MFMA backward exists in four forms.  STORED (the layer's default): a dK/dV kernel that forms S, dP and dS once and
+// also writes dS (bf16) to the scratch, and a dQ kernel that reads it back: 5 matrix products per tile pair, no atomics,
+// reproducible, about S * S bytes of scratch per (batch, head).  SPLIT: the same pair with a dQ kernel that recomputes
+// S and dP instead (7 products), same bits, no dS in the scratch.  FUSED: one key-stationary kernel forms S and dP
+// once and produces dK, dV and dQ (5 products); dQ partial sums go to private fp32 slots, one per worker, and a last
+// pass sums them: no atomics, reproducible.  FUSED_ATOMIC: the fused kernel adding dQ with fp32 atomics into one buffer.
+// S = 32768, 32 heads: 23.7 / 25.8 / 30.9 / 27.6 ms: the atomic units take 25.4 ms for the adds alone, the slots are 78 GB
+// of read-modify-write inside the MFMA loop, the recomputation is two more products; dS streamed once each way costs least.
+// ANY: only for sizing the scratch (enough for every form).
 enum { ATTN_BWD_SPLIT = 0, ATTN_BWD_FUSED = 1, ATTN_BWD_FUSED_ATOMIC = 2, ATTN_BWD_STORED = 3, ATTN_BWD_ANY = -1 };
 // workers (and fp32 dQ slots) per (batch, head) the fused form uses for this shape
 int attn_bwd_slots(int B, int S, int nh);
-// fp32 scratch of the MFMA backward: scaled lse and D, each padded to a multiple of 64 rows per (batch, head); with_slots:
-// followed by the dQ slots of the fused forms
+// fp32 scratch of the MFMA backward in the given form: scaled lse and D, each padded to a multiple of 64 rows per
+// (batch, head), followed by the dQ slots (fused forms) or the stored dS (STORED)
 size_t attn_bwd_mfma_scratch_floats(int B, int S, int nh, int form);
 // computes its own row statistics (scratch) from o, dO and lse.  rope_table != nullptr: q and k were rotated
 // (table [S, 64, 2] fp32 of cos, sin) and dq, dk come out as gradients of the unrotated q, k
