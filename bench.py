@@ -600,6 +600,15 @@ def run_diag(env):
             r = taw.taw_diag_dq_update_rate(buf, S, 32, mode)
             out["dq_update"][f"S={S}, 32 heads, {mname}"] = {"ms": round(r["ms"], 3), "G_updates_per_s": round(r["updates_per_s"] / 1e9, 1)}
         del buf
+    # vector stores amid MFMAs: ns per trip of {16 or 64 MFMAs, then n stores of one KiB} per wavefront, 4 or 8 wavefronts per compute unit
+    nb = taw.taw_diag_store_cost_bytes()
+    buf = torch.empty(nb, dtype=torch.uint8, device="cuda")
+    out["store_cost_ns_per_trip"] = {}
+    for waves in (4, 8):
+        for mf in (16, 64):
+            row = {f"{n} stores": round(taw.taw_diag_store_cost(buf, nb, waves, mf, n), 1) for n in (0, 1, 2, 4)}
+            out["store_cost_ns_per_trip"][f"{waves} wavefronts per compute unit, {mf} MFMAs per trip"] = row
+    del buf
     # the product GEMM (NT, bf16, K = 4096) on 64, 256 and 1024 output tiles: the same kernel and the same work per tile; what changes
     # is how many compute units draw power at once
     BF = taw.TAW_BF16

@@ -49,6 +49,14 @@ int taw_diag_lds_read_rate(int32_t instr, int32_t waves, double* bytes_per_clock
  * (what a private slot allows).  buf: S * n_heads * 128 floats (overwritten).  *updates_per_s counts 4-byte elements. */
 int taw_diag_dq_update_rate(float* buf, int32_t S, int32_t n_heads, int32_t mode, double* updates_per_s, double* ms);
 
+/* What a vector store costs a SIMD that is otherwise issuing MFMAs (the question behind the attention backward that
+ * hands dS from one kernel to the other through memory): 256 workgroups of `waves` (4 or 8) wavefronts, each running
+ * 20000 trips of {`mfmas` (16 or 64) MFMAs, then `stores` (0, 1, 2 or 4) non-temporal stores of one contiguous KiB}.
+ * buf: device, taw_diag_store_cost_bytes() bytes (128 MiB: a 64 KiB window per wavefront), overwritten.
+ * *ns_per_trip: duration of the launch over the trips.  The difference to stores = 0 is what the stores cost. */
+size_t taw_diag_store_cost_bytes(void);
+int taw_diag_store_cost(void* buf, size_t buf_bytes, int32_t waves, int32_t mfmas, int32_t stores, double* ns_per_trip);
+
 /* How vector instructions issue beside MFMAs on one SIMD: core-clock cycles per slot of {one MFMA + nvalu vector instructions}.
  * mode 0: one wavefront per SIMD runs both; mode 1: two wavefronts per SIMD, each runs both; mode 2: two wavefronts per SIMD,
  * one issues only the MFMAs, the other only the vector instructions.  kind 0: v_fma_f32, 1: v_exp_f32.  nvalu: 0, 2, 4 or 8.

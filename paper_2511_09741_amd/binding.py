@@ -78,6 +78,8 @@ _SIGS = {
     "taw_diag_dq_update_rate": (C.c_int, [_vp, _i32, _i32, _i32, C.POINTER(C.c_double), C.POINTER(C.c_double)]),
     "taw_diag_gemm_tile_order": (C.c_int, [_i32, _i32, C.POINTER(C.c_int32), C.POINTER(C.c_int32)]),
     "taw_diag_issue_rate": (C.c_int, [_i32, _i32, _i32, C.POINTER(C.c_double), C.POINTER(C.c_double)]),
+    "taw_diag_store_cost_bytes": (C.c_size_t, []),
+    "taw_diag_store_cost": (C.c_int, [_vp, C.c_size_t, _i32, _i32, _i32, C.POINTER(C.c_double)]),
     "taw_status_string": (C.c_char_p, [C.c_int]),
     "taw_last_error": (C.c_char_p, []),
     "taw_op_gemm": (C.c_int, [_i32, _i32, _i64, _i64, _i64, _vp, _i64, _vp, _i64, _vp, _i64, _i32, _i32, _vp, _i64, _i32, _vp]),
@@ -335,6 +337,16 @@ def taw_diag_gemm_tile_order(tiles_m, tiles_n):
     rows, cols = (C.c_int32 * n)(), (C.c_int32 * n)()
     _check(load().taw_diag_gemm_tile_order(tiles_m, tiles_n, rows, cols))
     return list(rows), list(cols)
+
+
+def taw_diag_store_cost_bytes() -> int:
+    return int(load().taw_diag_store_cost_bytes())
+
+
+def taw_diag_store_cost(buf, buf_bytes, waves, mfmas, stores) -> float:
+    a = C.c_double()
+    _check(load().taw_diag_store_cost(_p(buf), buf_bytes, waves, mfmas, stores, C.byref(a)))
+    return a.value
 
 
 def taw_diag_issue_rate(mode, kind, nvalu) -> dict:

@@ -334,6 +334,71 @@ extern "C" int taw_diag_dq_update_rate(float* buf, int32_t S, int32_t n_heads, i
   return TAW_OK;
 }
 
+// ---- what a vector store costs a SIMD that is otherwise issuing MFMAs -------------------------------------------------
+// Every wavefront: `iters` trips of NM MFMAs (four independent accumulators) followed by NS non-temporal stores of one
+// contiguous KiB (16 bytes per lane) into a 64 KiB window of its own, walked KiB by KiB.
+template <int NM, int NS>
+__global__ void __launch_bounds__(512, 1) store_cost_kernel(unsigned char* __restrict__ buf, int iters, float* __restrict__ sink) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
+  unsigned char* win = buf + ((size_t)blockIdx.x * nw + wave) * 65536;
+  bf16x8_t a, b;
+  unsigned x = (threadIdx.x + blockIdx.x * 977u) * 2654435761u;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    x = x * 1664525u + 1013904223u;
+    a[i] = (bf16_t)(((x >> 9) & 255) / 256.0f + 0.06f);
+    x = x * 1664525u + 1013904223u;
+    b[i] = (bf16_t)(((x >> 9) & 255) / 256.0f - 0.5f);
+  }
+  f32x16_t acc[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[j][r] = 0.f;
+  u32x4_t v = {x, x + 1, x + 2, x + 3};
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int m = 0; m < NM; ++m) acc[m & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[m & 3], 0, 0, 0);
+#pragma unroll
+    for (int st = 0; st < NS; ++st) {
+      unsigned char* p = win + ((((it & 63) * 1024) + st * 16384) & 65535) + lane * 16;      // at most 64512 + 1008 + 16 bytes into the window
+      __builtin_nontemporal_store(v, reinterpret_cast<u32x4_t*>(p));
+    }
+    v[0] += 1;
+    __builtin_amdgcn_sched_barrier(0);
+  }
+  float t = 0.f;
+#pragma unroll
+  for (int j = 0; j < 4; ++j)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) t += acc[j][r];
+  if (t == 12345.678f) sink[0] = t;
+}
+
+extern "C" size_t taw_diag_store_cost_bytes(void) { return (size_t)256 * 8 * 65536; }
+
+extern "C" int taw_diag_store_cost(void* buf, size_t buf_bytes, int32_t waves, int32_t mfmas, int32_t stores, double* ns_per_trip) {
+  if (!buf || !ns_per_trip) return TAW_ERR_NULL;
+  if ((reinterpret_cast<uintptr_t>(buf) & 15u) != 0) return TAW_ERR_ALIGN;
+  if (buf_bytes < taw_diag_store_cost_bytes()) return TAW_ERR_WORKSPACE;       // 256 workgroups x 8 wavefronts x 64 KiB, whatever `waves` is
+  if ((waves != 4 && waves != 8) || (mfmas != 16 && mfmas != 64) || (stores != 0 && stores != 1 && stores != 2 && stores != 4)) return TAW_ERR_SHAPE;
+  void* p = nullptr;
+  if (hipGetSymbolAddress(&p, HIP_SYMBOL(g_clk)) != hipSuccess) return TAW_ERR_HIP;
+  float* sink = reinterpret_cast<float*>(p) + 64;
+  const int iters = 20000;
+  float ms = 0.f;
+  int rc = -1;
+#define TAW_DIAG_STORE(M, N)                                                                                                 \
+  if (mfmas == M && stores == N)                                                                                             \
+    rc = timed([&] { hipLaunchKernelGGL((store_cost_kernel<M, N>), dim3(256), dim3(waves * 64), 0, 0, static_cast<unsigned char*>(buf), iters, sink); }, &ms);
+  TAW_DIAG_STORE(16, 0) TAW_DIAG_STORE(16, 1) TAW_DIAG_STORE(16, 2) TAW_DIAG_STORE(16, 4)
+  TAW_DIAG_STORE(64, 0) TAW_DIAG_STORE(64, 1) TAW_DIAG_STORE(64, 2) TAW_DIAG_STORE(64, 4)
+#undef TAW_DIAG_STORE
+  if (rc) return TAW_ERR_HIP;
+  *ns_per_trip = (double)ms * 1e6 / iters;
+  return TAW_OK;
+}
+
 extern "C" int taw_diag_gemm_tile_order(int32_t tiles_m, int32_t tiles_n, int32_t* tile_rows, int32_t* tile_cols) {
   if (tiles_m < 1 || tiles_n < 1 || (int64_t)tiles_m * tiles_n > (1 << 24)) return TAW_ERR_SHAPE;
   if (!tile_rows || !tile_cols) return TAW_ERR_NULL;

@@ -31,7 +31,7 @@ def declared_functions():
 
 def test_every_declared_symbol_is_exported(lib):
     names = declared_functions()
-    assert len(names) == 35
+    assert len(names) == 37
     for n in names:
         assert hasattr(lib, n), f"{n} declared in include/ but not exported"
     assert set(names) == set(taw.EXPORTS)
@@ -222,6 +222,13 @@ def test_diag_validation(lib):
     assert e.value.status == taw.TAW_ERR_SHAPE
     with pytest.raises(taw.TawError) as e:
         taw.taw_diag_issue_rate(3, 0, 4)
+    assert e.value.status == taw.TAW_ERR_SHAPE
+    assert taw.taw_diag_store_cost_bytes() == 256 * 8 * 65536
+    with pytest.raises(taw.TawError) as e:
+        taw.taw_diag_store_cost(0x10000, 1 << 20, 8, 16, 1)                  # the buffer must hold every wavefront's window
+    assert e.value.status == taw.TAW_ERR_WORKSPACE
+    with pytest.raises(taw.TawError) as e:
+        taw.taw_diag_store_cost(0x10000, taw.taw_diag_store_cost_bytes(), 8, 32, 1)
     assert e.value.status == taw.TAW_ERR_SHAPE
     with pytest.raises(taw.TawError) as e:
         taw.taw_diag_issue_rate(0, 0, 3)                             # 0, 2, 4 or 8 vector instructions per slot
