@@ -40,7 +40,7 @@ Prints ONE JSON line.  Besides the contract fields it carries
   measured_ceiling  a loop of nothing but bf16 MFMAs on random operands, timed in the same run: what the matrix cores
                 sustain under the part's power limit; every TFLOP/s roofline carries its fraction of that too
 --workload diag prints the probes of include/taw_diag.h instead (MFMA loop alone, with LDS reads, with loads; LDS read
-rate; dQ-update rates with atomics, stores, load-add-store; the GEMM kernel on 64 / 256 / 1024 tiles).
+rate; dQ-update rates with atomics, stores, load-add-store; vector stores beside MFMAs; the GEMM kernel on 64 / 256 / 1024 tiles and over K).
 """
 from __future__ import annotations
 
