@@ -57,6 +57,14 @@ int taw_diag_dq_update_rate(float* buf, int32_t S, int32_t n_heads, int32_t mode
 size_t taw_diag_store_cost_bytes(void);
 int taw_diag_store_cost(void* buf, size_t buf_bytes, int32_t waves, int32_t mfmas, int32_t stores, double* ns_per_trip);
 
+/* Host only: the layout of the dS matrix that the default attention backward hands from its dK/dV kernel to its dQ
+ * kernel, for sequence length S (1 .. 2^20), as the kernels compute it.  nqt = ceil(S / 256) blocks of query rows.
+ * *pair_bytes: bytes per (batch, head).  unit_offsets[]: byte offset of every 2 KiB unit, in the order block ib, 32-row
+ * group s = 0..7, key group g = 0 .. 8 (ib + 1) - 1: 32 nqt (nqt + 1) entries.  slots[(2 tt + hh) * 32 + kk]: the 16-byte
+ * slot (0..127) inside a unit that lane (key kk, lane half hh) of the writer gives its piece tt.  rows[p]: the query row
+ * (0..31 of its group) at position p = 16 hh + 8 tt + e of a key's 32 values.  All host pointers. */
+int taw_diag_attn_ds_layout(int32_t S, int64_t* pair_bytes, int64_t* unit_offsets, int32_t* slots, int32_t* rows);
+
 /* How vector instructions issue beside MFMAs on one SIMD: core-clock cycles per slot of {one MFMA + nvalu vector instructions}.
  * mode 0: one wavefront per SIMD runs both; mode 1: two wavefronts per SIMD, each runs both; mode 2: two wavefronts per SIMD,
  * one issues only the MFMAs, the other only the vector instructions.  kind 0: v_fma_f32, 1: v_exp_f32.  nvalu: 0, 2, 4 or 8.

@@ -78,6 +78,7 @@ _SIGS = {
     "taw_diag_dq_update_rate": (C.c_int, [_vp, _i32, _i32, _i32, C.POINTER(C.c_double), C.POINTER(C.c_double)]),
     "taw_diag_gemm_tile_order": (C.c_int, [_i32, _i32, C.POINTER(C.c_int32), C.POINTER(C.c_int32)]),
     "taw_diag_issue_rate": (C.c_int, [_i32, _i32, _i32, C.POINTER(C.c_double), C.POINTER(C.c_double)]),
+    "taw_diag_attn_ds_layout": (C.c_int, [_i32, C.POINTER(C.c_int64), C.POINTER(C.c_int64), C.POINTER(C.c_int32), C.POINTER(C.c_int32)]),
     "taw_diag_store_cost_bytes": (C.c_size_t, []),
     "taw_diag_store_cost": (C.c_int, [_vp, C.c_size_t, _i32, _i32, _i32, C.POINTER(C.c_double)]),
     "taw_status_string": (C.c_char_p, [C.c_int]),
@@ -337,6 +338,17 @@ def taw_diag_gemm_tile_order(tiles_m, tiles_n):
     rows, cols = (C.c_int32 * n)(), (C.c_int32 * n)()
     _check(load().taw_diag_gemm_tile_order(tiles_m, tiles_n, rows, cols))
     return list(rows), list(cols)
+
+
+def taw_diag_attn_ds_layout(S) -> dict:
+    nqt = (S + 255) // 256
+    n = 32 * nqt * (nqt + 1)
+    pair = C.c_int64()
+    offs = (C.c_int64 * max(n, 1))()
+    slots = (C.c_int32 * 128)()
+    rows = (C.c_int32 * 32)()
+    _check(load().taw_diag_attn_ds_layout(S, C.byref(pair), offs, slots, rows))
+    return {"pair_bytes": pair.value, "unit_offsets": list(offs)[:n], "slots": list(slots), "rows": list(rows)}
 
 
 def taw_diag_store_cost_bytes() -> int:

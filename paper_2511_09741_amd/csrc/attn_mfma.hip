@@ -584,11 +584,7 @@ constexpr size_t kKvLds = kKvOffRing + 2 * kKvStage;
 // The stores cost this kernel 13 % (16.3 instead of 14.4 ms at S = 32768, 32 heads) wherever in the loop they are issued,
 // whether the next iteration's wait for loads also waits for them or not, and whether they go to 35 GB of memory or
 // over and over to the same few KiB: it is the issue of the store instructions that costs, not the traffic.
-constexpr int64_t kDsBlockBytes = 256 * 256 * 2;       // one (256 keys, 256 query rows) block
-__host__ __device__ inline int64_t ds_block_offset(int ib) { return (int64_t)ib * (ib + 1) / 2 * kDsBlockBytes; }     // blocks 0 .. ib-1 hold 256 (i + 1) keys each
-__host__ __device__ inline int64_t ds_unit_offset(int ib, int s, int g) { return ds_block_offset(ib) + ((int64_t)s * 8 * (ib + 1) + g) * 2048; }
-__device__ __forceinline__ unsigned ds_slot(int kk, int hh, int tt) { return (unsigned)(tt * 64 + ((((kk >> 2) * 8) + (kk & 3) * 2 + hh) ^ (tt * 8))); }
-__device__ __forceinline__ int ds_row_of_slot(int slot) { return 16 * ((slot >> 3) & 1) + 4 * (slot >> 4) + (slot & 3) + 8 * ((slot >> 2) & 1); }
+// (ds_block_offset, ds_unit_offset, ds_slot, ds_row_of_slot: taw_internal.h, where host code can check them)
 
 template <bool STORE_DS>
 __global__ void __launch_bounds__(kThreads8, 1)

@@ -411,6 +411,22 @@ extern "C" int taw_diag_gemm_tile_order(int32_t tiles_m, int32_t tiles_n, int32_
   return TAW_OK;
 }
 
+extern "C" int taw_diag_attn_ds_layout(int32_t S, int64_t* pair_bytes, int64_t* unit_offsets, int32_t* slots, int32_t* rows) {
+  if (S < 1 || S > (1 << 20)) return TAW_ERR_SHAPE;
+  if (!pair_bytes || !unit_offsets || !slots || !rows) return TAW_ERR_NULL;
+  const int nqt = (S + 255) / 256;
+  *pair_bytes = taw::ds_block_offset(nqt);
+  size_t n = 0;
+  for (int ib = 0; ib < nqt; ++ib)
+    for (int s8 = 0; s8 < 8; ++s8)
+      for (int g = 0; g < 8 * (ib + 1); ++g) unit_offsets[n++] = taw::ds_unit_offset(ib, s8, g);
+  for (int tt = 0; tt < 2; ++tt)
+    for (int hh = 0; hh < 2; ++hh)
+      for (int kk = 0; kk < 32; ++kk) slots[(tt * 2 + hh) * 32 + kk] = (int32_t)taw::ds_slot(kk, hh, tt);
+  for (int p = 0; p < 32; ++p) rows[p] = taw::ds_row_of_slot(p);
+  return TAW_OK;
+}
+
 extern "C" int taw_diag_issue_rate(int32_t mode, int32_t kind, int32_t nvalu, double* cycles_mfma_wave, double* cycles_valu_wave) {
   if (!cycles_mfma_wave || !cycles_valu_wave) return TAW_ERR_NULL;
   if (mode < 0 || mode > 2 || kind < 0 || kind > 1 || (nvalu != 0 && nvalu != 2 && nvalu != 4 && nvalu != 8)) return TAW_ERR_SHAPE;

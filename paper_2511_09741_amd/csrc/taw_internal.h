@@ -134,6 +134,17 @@ int launch_attn_fwd_mfma(int B, int S, int nh, const void* qkv, void* o, float* 
 // of read-modify-write inside the MFMA loop, the recomputation is two more products; dS streamed once each way costs least.
 // ANY: only for sizing the scratch (enough for every form).
 enum { ATTN_BWD_SPLIT = 0, ATTN_BWD_FUSED = 1, ATTN_BWD_FUSED_ATOMIC = 2, ATTN_BWD_STORED = 3, ATTN_BWD_ANY = -1 };
+// ---- layout of the stored dS (ATTN_BWD_STORED), shared by the kernel that writes it, the kernel that reads it and the host
+// Per (batch, head): block ib of 256 query rows holds 256 (ib + 1) keys x 256 rows bf16, blocks one after the other; inside a
+// block, per 32-row group s, the 2 KiB units dS[32 rows][32 keys] of the key groups g = 0 .. 8 (ib + 1) - 1 one after the
+// other.  Inside a unit, 128 slots of 16 bytes: lane (key kk, lane half hh) of the writing wavefront puts its piece tt
+// (8 bf16 = accumulator registers 8 tt .. 8 tt + 7) at slot ds_slot(kk, hh, tt); position p = 16 hh + 8 tt + e of a
+// key's 32 values is query row ds_row_of_slot(p) of the group.
+constexpr int64_t kDsBlockBytes = 256 * 256 * 2;       // one (256 keys, 256 query rows) block
+__host__ __device__ inline int64_t ds_block_offset(int ib) { return (int64_t)ib * (ib + 1) / 2 * kDsBlockBytes; }
+__host__ __device__ inline int64_t ds_unit_offset(int ib, int s, int g) { return ds_block_offset(ib) + ((int64_t)s * 8 * (ib + 1) + g) * 2048; }
+__host__ __device__ inline unsigned ds_slot(int kk, int hh, int tt) { return (unsigned)(tt * 64 + ((((kk >> 2) * 8) + (kk & 3) * 2 + hh) ^ (tt * 8))); }
+__host__ __device__ inline int ds_row_of_slot(int p) { return 16 * ((p >> 3) & 1) + 4 * (p >> 4) + (p & 3) + 8 * ((p >> 2) & 1); }
 // workers (and fp32 dQ slots) per (batch, head) the fused form uses for this shape
 int attn_bwd_slots(int B, int S, int nh);
 // fp32 scratch of the MFMA backward in the given form: scaled lse and D, each padded to a multiple of 64 rows per

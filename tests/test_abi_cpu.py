@@ -31,7 +31,7 @@ def declared_functions():
 
 def test_every_declared_symbol_is_exported(lib):
     names = declared_functions()
-    assert len(names) == 37
+    assert len(names) == 38
     for n in names:
         assert hasattr(lib, n), f"{n} declared in include/ but not exported"
     assert set(names) == set(taw.EXPORTS)
@@ -300,3 +300,38 @@ def test_workspace_size_follows_the_attention_backward_form(lib):
         assert full - lean == cfg.B * cfg.n_heads * (nqt * (nqt + 1) // 2) * 256 * 256 * 2
     c1 = I.CONFIGS["C1"]
     assert taw.taw_layer_workspace_bytes(taw.desc_from_config(c1, 0)) == taw.taw_layer_workspace_bytes(taw.desc_from_config(c1, taw.TAW_ATTN_BWD_RECOMPUTE))
+
+
+@pytest.mark.parametrize("S", [1, 255, 256, 257, 1100, 4096])
+def test_stored_ds_layout(lib, S):
+    """The dS hand-over of the default attention backward, as the kernels address it: the 2 KiB units of a (batch, head) tile
+    its region exactly (no gap, no overlap, query block ib holding 256 (ib + 1) keys x 256 rows), and a wavefront of the reading
+    kernel (one 32-row group) finds its units for consecutive key groups at consecutive addresses; the 128 slots of a unit are a
+    permutation, each store instruction (one piece of all 64 lanes) fills one contiguous KiB, and the 16 slots a
+    half-wavefront of the reader touches in one transposing read (4 consecutive keys x 2 lane halves x 2 pieces) fall into 16
+    different 16-byte bank groups; positions map back to the accumulator's row order."""
+    L = taw.taw_diag_attn_ds_layout(S)
+    nqt = (S + 255) // 256
+    assert L["pair_bytes"] == sum(256 * (ib + 1) * 256 * 2 for ib in range(nqt))
+    offs = L["unit_offsets"]
+    assert sorted(offs) == list(range(0, L["pair_bytes"], 2048))
+    k = 0
+    for ib in range(nqt):
+        for s in range(8):
+            run = offs[k:k + 8 * (ib + 1)]
+            assert run == list(range(run[0], run[0] + 2048 * len(run), 2048))
+            k += len(run)
+    slots = L["slots"]
+    assert sorted(slots) == list(range(128))
+    for tt in range(2):
+        assert sorted(slots[(2 * tt + hh) * 32 + kk] for hh in range(2) for kk in range(32)) == list(range(64 * tt, 64 * tt + 64))
+    for k4 in range(8):
+        group = [slots[(2 * tt + hh) * 32 + 4 * k4 + j] for tt in range(2) for hh in range(2) for j in range(4)]
+        assert sorted(x % 16 for x in group) == list(range(16))
+    # position p = 16 hh + 8 tt + e holds accumulator register 8 tt + e of lane half hh, i.e. row 8 (r // 4) + 4 hh + r % 4
+    for hh in range(2):
+        for tt in range(2):
+            for e in range(8):
+                r = 8 * tt + e
+                assert L["rows"][16 * hh + 8 * tt + e] == 8 * (r // 4) + 4 * hh + r % 4
+    assert sorted(L["rows"]) == list(range(32))
