@@ -579,8 +579,10 @@ constexpr size_t kKvLds = kKvOffRing + 2 * kKvStage;
 // (ds_row_of_slot gives the row for the position 16 hh + 8 tt + e the dQ kernel sees it at).  Piece tt goes to slot
 // ds_slot(kk, hh, tt): the 64 lanes of one store instruction fill one contiguous KiB, and the dQ kernel, which copies
 // units into LDS as they are, reads them back by transposing reads without bank conflicts (the 16 slots one half-wavefront
-// reads - 4 keys x 2 lane halves x 2 pieces - differ in their low 4 bits).  Blocks of queries in front of the keys are
-// never written and never read.
+// reads - 4 keys x 2 lane halves x 2 pieces - differ in their low 4 bits).  Units whose 32 queries all lie in front of
+// their 32 keys (dS = 0 there) are never written; the dQ kernel copies the ones inside its diagonal block into LDS along
+// with the rest of a tile but never feeds them to an MFMA.  Likewise the units of row groups at or beyond S rounded up to
+// 64: what is read there only reaches rows of dQ that are not stored.  The caller clears nothing.
 // The stores cost this kernel 13 % (16.3 instead of 14.4 ms at S = 32768, 32 heads) wherever in the loop they are issued,
 // whether the next iteration's wait for loads also waits for them or not, and whether they go to 35 GB of memory or
 // over and over to the same few KiB: it is the issue of the store instructions that costs, not the traffic.
